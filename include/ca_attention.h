@@ -1,0 +1,131 @@
+/*
+ * ca_attention.h - C ABI of the attention-server compute step of core attention disaggregation
+ * on one MI355X (gfx950).
+ *
+ * The operation: causal core attention, P = softmax(scale * Q K^T) with masking, O = P V
+ * (Section 2.1, "Context-dependent layers"), forward and backward, over ONE fused launch of many
+ * CA-tasks.  A CA-task is a query shard q(t) of one document attending to that document's KV
+ * prefix kv(t) = context(q(t)) (Section 4.1, definition of the CA-task); an attention server
+ * receives {q(t), kv(t)} for its tasks, runs them all in a single kernel and returns each task's
+ * output (Section 4.1, runtime).  Forward keeps only O and one log-sum-exp per (row, head); backward
+ * recomputes P from it (Section 2.1: P is never materialised).
+ *
+ * All tensor pointers are DEVICE pointers owned by the caller; all descriptor arrays are HOST
+ * pointers.  No entry point synchronises the device or throws; every one returns CA_OK (0) or a
+ * negative ca_status, and ca_last_error() then holds a human-readable detail for the calling thread.
+ *
+ * Layouts (row-major, token-major, bf16 unless stated):
+ *   Q, O, dO, dQ : [total_q ][n_q_heads ][head_dim]
+ *   K, V, dK, dV : [total_kv][n_kv_heads][head_dim]
+ *   LSE          : [n_q_heads][total_q] fp32, natural log of the row's sum of exp(scale * score)
+ * Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *
+ * Semantics: row i of task t sits at document position p = q_pos[t] + i and attends keys
+ * j in [0, min(kv_len[t], p + 1)) of its document, i.e. packed KV rows doc_kv_start + j: causal inside
+ * the document, diagonal included, nothing across documents (Appendix B's shard geometry,
+ * n_q + L_kv - L_q <= n_kv <= L_kv).  Tasks of one document share that document's single KV range;
+ * dK/dV are gradients with respect to the packed KV buffer (summed over all tasks and all query heads
+ * of a group); KV rows no query attends receive 0.
+ */
+#ifndef CA_ATTENTION_H
+#define CA_ATTENTION_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CA_OK = 0,
+  CA_ERR_INVALID_ARG = -1, /* null pointer, bad count, range out of bounds, overlapping ranges, q_pos+q_len > kv_len ... */
+  CA_ERR_UNSUPPORTED = -2, /* head_dim not in {64,128}, n_q_heads not a multiple of n_kv_heads, sizes beyond int32 tiles */
+  CA_ERR_WORKSPACE = -3,   /* workspace null, too small or not 256-byte aligned */
+  CA_ERR_HIP = -4,         /* a HIP runtime call failed; detail string has its name and message */
+  CA_ERR_STATE = -5        /* plan not uploaded to a device, or used on a different device */
+} ca_status;
+
+typedef struct ca_plan ca_plan_t; /* opaque */
+
+/* One fused batch of CA-tasks (Section 4.1).  All arrays are host memory and are copied by ca_plan. */
+typedef struct {
+  int32_t n_docs, n_tasks;
+  int32_t n_q_heads, n_kv_heads, head_dim; /* n_q_heads % n_kv_heads == 0; head_dim 64 or 128 */
+  int64_t total_q, total_kv;               /* rows of packed Q/O/dO/dQ and of packed K/V/dK/dV */
+  float softmax_scale;                     /* <= 0 selects 1/sqrt(head_dim) */
+  const int64_t *doc_kv_start;             /* [n_docs] packed KV row of the document's token 0 */
+  const int64_t *doc_kv_len;               /* [n_docs] resident KV rows of the document (>= 1) */
+  const int32_t *task_doc;                 /* [n_tasks] */
+  const int64_t *task_q_start;             /* [n_tasks] first row in packed Q */
+  const int64_t *task_q_len;               /* [n_tasks] n_q >= 1, any integer */
+  const int64_t *task_q_pos;               /* [n_tasks] document position of the first query row */
+  const int64_t *task_kv_len;              /* [n_tasks] prefix attended: q_pos+q_len <= kv_len <= doc_kv_len */
+} ca_batch_desc;
+
+/*
+ * ca_plan_host: validate the descriptor and build the launch schedule on the host only (no HIP call):
+ * per-document sorted query-row lists cut into tiles (rows of different tasks of one document may
+ * share a tile; rows of different documents never do), forward work units (tile x head) and backward
+ * work units (KV tile x KV head) ordered longest-first.  Usable on a machine without a GPU and from a
+ * scheduler thread that prepares the next batch while the GPU runs the current one (Section 4.1: the
+ * scheduler works one batch ahead).  The plan owns copies of everything; free with ca_plan_destroy.
+ */
+int ca_plan_host(const ca_batch_desc *desc, ca_plan_t **out);
+
+/* ca_plan_upload: allocate the plan's small device arrays on the current device and copy the schedule
+ * (asynchronously on `hip_stream`, a hipStream_t or NULL for the default stream). */
+int ca_plan_upload(ca_plan_t *plan, void *hip_stream);
+
+/* ca_plan = ca_plan_host + ca_plan_upload on the default stream. */
+int ca_plan(const ca_batch_desc *desc, ca_plan_t **out);
+
+/* Bytes of caller-provided device workspace ca_forward / ca_backward need (either pointer may be NULL). */
+int ca_plan_workspace_bytes(const ca_plan_t *plan, size_t *fwd_bytes, size_t *bwd_bytes);
+
+/*
+ * ca_forward: O and LSE for every query row of every task, one fused launch on `hip_stream`.
+ * q,k,v: device bf16 inputs; o: device bf16 output; lse: device fp32 output [n_q_heads][total_q].
+ * ws: device workspace of at least fwd_bytes (may be NULL when fwd_bytes is 0), 256-byte aligned.
+ * Allocates nothing, never synchronises.
+ */
+int ca_forward(const ca_plan_t *plan, const void *q, const void *k, const void *v, void *o, float *lse,
+               void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * ca_backward: dQ, dK, dV of L = sum(dO * O) given the forward's inputs and its saved O and LSE
+ * (nothing else is kept between the two calls).  dq like q; dk, dv like k, v (every row written).
+ * ws: device workspace of at least bwd_bytes, 256-byte aligned.  dQ is accumulated with floating-point
+ * atomics, so its low-order bits may differ from run to run.  Allocates nothing, never synchronises.
+ */
+int ca_backward(const ca_plan_t *plan, const void *q, const void *k, const void *v, const void *o,
+                const void *d_o, const float *lse, void *dq, void *dk, void *dv,
+                void *ws, size_t ws_bytes, void *hip_stream);
+
+void ca_plan_destroy(ca_plan_t *plan);
+
+const char *ca_error_string(int code);
+const char *ca_last_error(void); /* thread-local detail of the last failing call on this thread */
+
+/*
+ * Schedule introspection (host side; for tests, profilers and cost models).
+ * ca_plan_info fills `out[0..n)` with, in order: q_tile_rows, n_q_tiles, n_fwd_units, kv_tile_rows,
+ * n_bwd_units, fwd_kv_step, padded_rows, sum over forward units of KV steps, sum over backward units of
+ * (q blocks x heads) steps, bwd_q_block_rows.  Returns the number of values available.
+ */
+int ca_plan_info(const ca_plan_t *plan, int64_t *out, int n);
+/* Copies of the schedule arrays.  Each returns the element count; pass NULL to query it.
+ *  rows : [padded_rows] packed Q row of each tile slot, -1 for padding
+ *  pos  : [padded_rows] document position of each tile slot
+ *  fwd  : [n_fwd_units][4] = {first slot, packed KV row of doc token 0, keys needed (max pos + 1), head}
+ *  bwd  : [n_bwd_units][6] = {first slot of first q block, slots end, packed KV row of the tile's first key,
+ *                             valid keys in tile, document position of the tile's first key, KV head}
+ */
+int64_t ca_plan_rows(const ca_plan_t *plan, int32_t *rows, int32_t *pos);
+int64_t ca_plan_fwd_units(const ca_plan_t *plan, int32_t *units);
+int64_t ca_plan_bwd_units(const ca_plan_t *plan, int32_t *units);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CA_ATTENTION_H */

@@ -1,0 +1,217 @@
+"""Thin Python binding over the C ABI of libca_attention.so (include/ca_attention.h).
+
+Argument marshalling only: every step of the path runs inside the library's HIP kernels.  PyTorch
+tensors are used as device memory and streams and nothing else.  There is no fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libca_attention.so")
+_lib = None
+
+CA_OK = 0
+CA_ERR_INVALID_ARG, CA_ERR_UNSUPPORTED, CA_ERR_WORKSPACE, CA_ERR_HIP, CA_ERR_STATE = -1, -2, -3, -4, -5
+
+
+class CaError(RuntimeError):
+    def __init__(self, code: int, detail: str):
+        super().__init__(f"ca_attention error {code}: {detail}")
+        self.code = code
+        self.detail = detail
+
+
+class BatchDesc(ctypes.Structure):
+    _fields_ = [
+        ("n_docs", ctypes.c_int32), ("n_tasks", ctypes.c_int32),
+        ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("total_q", ctypes.c_int64), ("total_kv", ctypes.c_int64), ("softmax_scale", ctypes.c_float),
+        ("doc_kv_start", ctypes.c_void_p), ("doc_kv_len", ctypes.c_void_p), ("task_doc", ctypes.c_void_p),
+        ("task_q_start", ctypes.c_void_p), ("task_q_len", ctypes.c_void_p), ("task_q_pos", ctypes.c_void_p),
+        ("task_kv_len", ctypes.c_void_p),
+    ]
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library; raises if it has not been built (python -m paper_2510_18121_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
+                                    "or python paper_2510_18121_amd/build.py")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        L.ca_plan_host.argtypes = [ctypes.POINTER(BatchDesc), ctypes.POINTER(vp)]
+        L.ca_plan.argtypes = [ctypes.POINTER(BatchDesc), ctypes.POINTER(vp)]
+        L.ca_plan_upload.argtypes = [vp, vp]
+        L.ca_plan_workspace_bytes.argtypes = [vp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+        L.ca_forward.argtypes = [vp] * 6 + [vp, sz, vp]
+        L.ca_backward.argtypes = [vp] * 10 + [vp, sz, vp]
+        L.ca_plan_destroy.argtypes = [vp]
+        L.ca_plan_destroy.restype = None
+        L.ca_error_string.argtypes = [ctypes.c_int]
+        L.ca_error_string.restype = ctypes.c_char_p
+        L.ca_last_error.restype = ctypes.c_char_p
+        L.ca_plan_info.argtypes = [vp, vp, ctypes.c_int]
+        for f in (L.ca_plan_rows, L.ca_plan_fwd_units, L.ca_plan_bwd_units):
+            f.restype = ctypes.c_int64
+        L.ca_plan_rows.argtypes = [vp, vp, vp]
+        L.ca_plan_fwd_units.argtypes = [vp, vp]
+        L.ca_plan_bwd_units.argtypes = [vp, vp]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != CA_OK:
+        raise CaError(rc, (lib().ca_last_error() or b"").decode())
+
+
+def make_desc(batch, keep: list) -> BatchDesc:
+    """ca_batch_desc from any object with the descriptor's field names (e.g. workloads.Batch)."""
+    def arr(x, dt):
+        a = np.ascontiguousarray(np.asarray(x), dtype=dt)
+        keep.append(a)
+        return a.ctypes.data if a.size else None
+
+    d = BatchDesc()
+    d.n_docs, d.n_tasks = len(batch.doc_kv_len), len(batch.task_q_len)
+    d.n_q_heads, d.n_kv_heads, d.head_dim = batch.n_q_heads, batch.n_kv_heads, batch.head_dim
+    d.total_q, d.total_kv, d.softmax_scale = batch.total_q, batch.total_kv, float(batch.softmax_scale)
+    d.doc_kv_start = arr(batch.doc_kv_start, np.int64)
+    d.doc_kv_len = arr(batch.doc_kv_len, np.int64)
+    d.task_doc = arr(batch.task_doc, np.int32)
+    d.task_q_start = arr(batch.task_q_start, np.int64)
+    d.task_q_len = arr(batch.task_q_len, np.int64)
+    d.task_q_pos = arr(batch.task_q_pos, np.int64)
+    d.task_kv_len = arr(batch.task_kv_len, np.int64)
+    return d
+
+
+class Plan:
+    """Owner of a ca_plan_t*."""
+
+    INFO_KEYS = ("q_tile_rows", "n_q_tiles", "n_fwd_units", "kv_tile_rows", "n_bwd_units", "fwd_kv_step",
+                 "padded_rows", "fwd_steps", "bwd_steps", "bwd_q_block_rows")
+
+    def __init__(self, handle, batch):
+        self.handle = ctypes.c_void_p(handle)
+        self.batch = batch
+
+    def upload(self, stream=None):
+        _check(lib().ca_plan_upload(self.handle, _stream_ptr(stream)))
+        return self
+
+    def workspace_bytes(self):
+        f, b = ctypes.c_size_t(), ctypes.c_size_t()
+        _check(lib().ca_plan_workspace_bytes(self.handle, ctypes.byref(f), ctypes.byref(b)))
+        return int(f.value), int(b.value)
+
+    def info(self) -> dict:
+        out = np.zeros(len(self.INFO_KEYS), np.int64)
+        lib().ca_plan_info(self.handle, out.ctypes.data, len(out))
+        return dict(zip(self.INFO_KEYS, out.tolist()))
+
+    def rows(self):
+        n = lib().ca_plan_rows(self.handle, None, None)
+        r, p = np.zeros(n, np.int32), np.zeros(n, np.int32)
+        lib().ca_plan_rows(self.handle, r.ctypes.data, p.ctypes.data)
+        return r, p
+
+    def fwd_units(self):
+        n = lib().ca_plan_fwd_units(self.handle, None)
+        u = np.zeros((n, 4), np.int32)
+        lib().ca_plan_fwd_units(self.handle, u.ctypes.data)
+        return u
+
+    def bwd_units(self):
+        n = lib().ca_plan_bwd_units(self.handle, None)
+        u = np.zeros((n, 6), np.int32)
+        lib().ca_plan_bwd_units(self.handle, u.ctypes.data)
+        return u
+
+    def destroy(self):
+        if self.handle:
+            lib().ca_plan_destroy(self.handle)
+            self.handle = ctypes.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def ca_plan_host(batch) -> Plan:
+    keep = []
+    d = make_desc(batch, keep)
+    h = ctypes.c_void_p()
+    _check(lib().ca_plan_host(ctypes.byref(d), ctypes.byref(h)))
+    return Plan(h.value, batch)
+
+
+def ca_plan(batch) -> Plan:
+    keep = []
+    d = make_desc(batch, keep)
+    h = ctypes.c_void_p()
+    _check(lib().ca_plan(ctypes.byref(d), ctypes.byref(h)))
+    return Plan(h.value, batch)
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        if torch.cuda.is_available():
+            return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        return ctypes.c_void_p(None)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _p(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None and t.numel() > 0 else ctypes.c_void_p(None)
+
+
+def _expect(t, shape, dtype, name):
+    if tuple(t.shape) != tuple(shape) or t.dtype != dtype or not t.is_contiguous() or not t.is_cuda:
+        raise ValueError(f"{name}: expected contiguous device tensor {tuple(shape)} {dtype}, got {tuple(t.shape)} {t.dtype}")
+
+
+def ca_forward(plan: Plan, q, k, v, o, lse, ws=None, stream=None):
+    """Launch the fused forward on torch's current stream (or `stream`).  Writes o (bf16) and lse (fp32)."""
+    import torch
+    b = plan.batch
+    _expect(q, (b.total_q, b.n_q_heads, b.head_dim), torch.bfloat16, "q")
+    _expect(k, (b.total_kv, b.n_kv_heads, b.head_dim), torch.bfloat16, "k")
+    _expect(v, (b.total_kv, b.n_kv_heads, b.head_dim), torch.bfloat16, "v")
+    _expect(o, (b.total_q, b.n_q_heads, b.head_dim), torch.bfloat16, "o")
+    _expect(lse, (b.n_q_heads, b.total_q), torch.float32, "lse")
+    wsb = ws.numel() * ws.element_size() if ws is not None else 0
+    _check(lib().ca_forward(plan.handle, _p(q), _p(k), _p(v), _p(o), _p(lse), _p(ws), wsb, _stream_ptr(stream)))
+
+
+def ca_backward(plan: Plan, q, k, v, o, d_o, lse, dq, dk, dv, ws, stream=None):
+    """Launch the backward on torch's current stream (or `stream`).  Writes dq, dk, dv (bf16)."""
+    import torch
+    b = plan.batch
+    qs, ks = (b.total_q, b.n_q_heads, b.head_dim), (b.total_kv, b.n_kv_heads, b.head_dim)
+    for t, s, n in ((q, qs, "q"), (o, qs, "o"), (d_o, qs, "d_o"), (dq, qs, "dq"), (k, ks, "k"), (v, ks, "v"),
+                    (dk, ks, "dk"), (dv, ks, "dv")):
+        _expect(t, s, torch.bfloat16, n)
+    _expect(lse, (b.n_q_heads, b.total_q), torch.float32, "lse")
+    wsb = ws.numel() * ws.element_size() if ws is not None else 0
+    _check(lib().ca_backward(plan.handle, _p(q), _p(k), _p(v), _p(o), _p(d_o), _p(lse), _p(dq), _p(dk), _p(dv),
+                             _p(ws), wsb, _stream_ptr(stream)))
+
+
+def alloc_workspace(plan: Plan, device="cuda"):
+    """A torch uint8 buffer big enough for both calls (torch's allocator returns 256-byte aligned blocks)."""
+    import torch
+    f, b = plan.workspace_bytes()
+    return torch.empty(max(f, b, 256), dtype=torch.uint8, device=device)

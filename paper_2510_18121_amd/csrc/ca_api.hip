@@ -1,0 +1,156 @@
+// C-ABI entry points that touch the device: plan upload, forward and backward launches.
+#include <hip/hip_runtime.h>
+
+#include <sstream>
+
+#include "ca_internal.h"
+
+namespace ca {
+hipError_t launch_fwd(const ca_plan_t *p, const void *q, const void *k, const void *v, void *o, float *lse,
+                      hipStream_t st);
+hipError_t launch_bwd(const ca_plan_t *p, const void *q, const void *k, const void *v, const void *o, const void *d_o,
+                      const float *lse, void *dq, void *dk, void *dv, void *ws, hipStream_t st);
+
+static int hip_fail(const char *what, hipError_t e) {
+  std::ostringstream os;
+  os << what << ": " << hipGetErrorName(e) << " (" << hipGetErrorString(e) << ")";
+  set_error(os.str());
+  return CA_ERR_HIP;
+}
+#define CA_HIP(call)                                  \
+  do {                                                \
+    hipError_t e_ = (call);                           \
+    if (e_ != hipSuccess) return hip_fail(#call, e_); \
+  } while (0)
+
+static void free_device(ca_plan_t *p) {
+  if (p->device < 0) return;
+  int cur = -1;
+  if (hipGetDevice(&cur) == hipSuccess && cur != p->device) (void)hipSetDevice(p->device);
+  if (p->d_slot_row) (void)hipFree(p->d_slot_row);
+  if (p->d_slot_pos) (void)hipFree(p->d_slot_pos);
+  if (p->d_fwd_units) (void)hipFree(p->d_fwd_units);
+  if (p->d_bwd_units) (void)hipFree(p->d_bwd_units);
+  p->d_slot_row = p->d_slot_pos = nullptr;
+  p->d_fwd_units = nullptr;
+  p->d_bwd_units = nullptr;
+  if (cur >= 0 && cur != p->device) (void)hipSetDevice(cur);
+  p->device = -1;
+}
+
+static int check_call(const ca_plan_t *p, void *ws, size_t ws_bytes, size_t need) {
+  if (!p) {
+    set_error("plan is null");
+    return CA_ERR_INVALID_ARG;
+  }
+  if (p->device < 0) {
+    set_error("plan was not uploaded (ca_plan_upload)");
+    return CA_ERR_STATE;
+  }
+  int cur = -1;
+  hipError_t e = hipGetDevice(&cur);
+  if (e != hipSuccess) return hip_fail("hipGetDevice", e);
+  if (cur != p->device) {
+    set_error("plan was uploaded to another device than the current one");
+    return CA_ERR_STATE;
+  }
+  if (need > 0) {
+    if (!ws || ws_bytes < need) {
+      std::ostringstream os;
+      os << "workspace of " << ws_bytes << " bytes given, " << need << " needed";
+      set_error(os.str());
+      return CA_ERR_WORKSPACE;
+    }
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) {
+      set_error("workspace is not 256-byte aligned");
+      return CA_ERR_WORKSPACE;
+    }
+  }
+  return CA_OK;
+}
+}  // namespace ca
+
+extern "C" {
+
+int ca_plan_upload(ca_plan_t *p, void *hip_stream) {
+  using namespace ca;
+  if (!p) {
+    set_error("plan is null");
+    return CA_ERR_INVALID_ARG;
+  }
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  free_device(p);
+  int dev = -1;
+  CA_HIP(hipGetDevice(&dev));
+  p->device = dev;
+  auto up = [&](auto *&dst, const auto &src) -> hipError_t {
+    if (src.empty()) return hipSuccess;
+    const size_t bytes = src.size() * sizeof(src[0]);
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&dst), bytes);
+    if (e != hipSuccess) return e;
+    return hipMemcpyAsync(dst, src.data(), bytes, hipMemcpyHostToDevice, st);
+  };
+  hipError_t e;
+  if ((e = up(p->d_slot_row, p->slot_row)) != hipSuccess || (e = up(p->d_slot_pos, p->slot_pos)) != hipSuccess ||
+      (e = up(p->d_fwd_units, p->fwd_units)) != hipSuccess || (e = up(p->d_bwd_units, p->bwd_units)) != hipSuccess) {
+    free_device(p);
+    return hip_fail("plan upload", e);
+  }
+  // the host vectors stay alive in the plan, so the asynchronous copies read valid memory
+  return CA_OK;
+}
+
+int ca_plan(const ca_batch_desc *desc, ca_plan_t **out) {
+  int rc = ca_plan_host(desc, out);
+  if (rc != CA_OK) return rc;
+  rc = ca_plan_upload(*out, nullptr);
+  if (rc != CA_OK) {
+    ca_plan_destroy(*out);
+    *out = nullptr;
+  }
+  return rc;
+}
+
+void ca_plan_destroy(ca_plan_t *p) {
+  if (!p) return;
+  ca::free_device(p);
+  delete p;
+}
+
+int ca_forward(const ca_plan_t *p, const void *q, const void *k, const void *v, void *o, float *lse, void *ws,
+               size_t ws_bytes, void *hip_stream) {
+  using namespace ca;
+  int rc = check_call(p, ws, ws_bytes, p ? p->ws_fwd : 0);
+  if (rc != CA_OK) return rc;
+  if (p->total_q > 0 && (!q || !o || !lse)) {
+    set_error("q, o or lse is null");
+    return CA_ERR_INVALID_ARG;
+  }
+  if (p->total_kv > 0 && (!k || !v)) {
+    set_error("k or v is null");
+    return CA_ERR_INVALID_ARG;
+  }
+  hipError_t e = launch_fwd(p, q, k, v, o, lse, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return hip_fail("forward launch", e);
+  return CA_OK;
+}
+
+int ca_backward(const ca_plan_t *p, const void *q, const void *k, const void *v, const void *o, const void *d_o,
+                const float *lse, void *dq, void *dk, void *dv, void *ws, size_t ws_bytes, void *hip_stream) {
+  using namespace ca;
+  int rc = check_call(p, ws, ws_bytes, p ? p->ws_bwd : 0);
+  if (rc != CA_OK) return rc;
+  if (p->total_q > 0 && (!q || !o || !d_o || !lse || !dq)) {
+    set_error("q, o, d_o, lse or dq is null");
+    return CA_ERR_INVALID_ARG;
+  }
+  if (p->total_kv > 0 && (!k || !v || !dk || !dv)) {
+    set_error("k, v, dk or dv is null");
+    return CA_ERR_INVALID_ARG;
+  }
+  hipError_t e = launch_bwd(p, q, k, v, o, d_o, lse, dq, dk, dv, ws, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return hip_fail("backward launch", e);
+  return CA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,62 @@
+// Internal definitions shared by the host planner, the launchers and the kernels.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "ca_attention.h"
+
+namespace ca {
+
+// Tile geometry.  Every document's sorted query rows occupy a run of "slots" padded to SLOT_ALIGN, so
+// that forward tiles (FWD_BM slots) and backward q blocks (BWD_BQ slots) both tile the same arrays.
+constexpr int SLOT_ALIGN = 128;
+constexpr int FWD_BM = 128;  // query rows per forward work unit (4 waves x 32)
+constexpr int FWD_BN = 64;   // keys per forward inner step
+constexpr int BWD_BN = 128;  // keys owned by one backward work unit (4 waves x 32)
+constexpr int BWD_BQ = 64;   // query rows per backward inner step
+
+struct FwdUnit {  // one (q tile, q head)
+  int32_t slot0;    // first slot of the tile
+  int32_t kv_row0;  // packed KV row of the document's token 0
+  int32_t n_keys;   // keys the tile needs: max position + 1
+  int32_t head;
+};
+
+struct BwdUnit {  // one (KV tile, KV head)
+  int32_t slot_begin;  // first slot of the first q block that sees this KV tile
+  int32_t slot_end;    // end of the document's slots
+  int32_t kv_row;      // packed KV row of the tile's first key
+  int32_t n_valid;     // valid keys in the tile
+  int32_t key_pos0;    // document position of the tile's first key
+  int32_t kv_head;
+};
+
+}  // namespace ca
+
+struct ca_plan {
+  // descriptor copy
+  int32_t n_docs = 0, n_tasks = 0, hq = 0, hkv = 0, d = 0;
+  int64_t total_q = 0, total_kv = 0;
+  float scale = 0.f;
+  std::vector<int64_t> doc_kv_start, doc_kv_len, task_q_start, task_q_len, task_q_pos, task_kv_len;
+  std::vector<int32_t> task_doc;
+  // schedule (host)
+  std::vector<int32_t> slot_row, slot_pos;
+  std::vector<ca::FwdUnit> fwd_units;
+  std::vector<ca::BwdUnit> bwd_units;
+  int64_t fwd_steps = 0, bwd_steps = 0;
+  // workspace layout for backward: [dq_acc fp32 total_q*hq*d][delta fp32 hq*total_q]
+  size_t ws_fwd = 0, ws_bwd = 0, ws_off_delta = 0;
+  // device copies
+  int device = -1;
+  int32_t *d_slot_row = nullptr, *d_slot_pos = nullptr;
+  ca::FwdUnit *d_fwd_units = nullptr;
+  ca::BwdUnit *d_bwd_units = nullptr;
+};
+
+namespace ca {
+void set_error(const std::string &msg);
+int build_plan(const ca_batch_desc *desc, ca_plan_t **out);  // host only
+}  // namespace ca

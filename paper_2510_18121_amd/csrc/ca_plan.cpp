@@ -1,0 +1,296 @@
+// Host-side planner: descriptor validation and the tile schedule.  Pure C++, no HIP calls.
+//
+// The mask of a query row depends only on its document position p (it sees keys 0..p of its own
+// document; Appendix B's shard geometry), not on which CA-task carried it.  So the planner forgets task
+// boundaries: per document it lists every query row present in the batch sorted by position and cuts
+// that list into tiles.  Rows of different tasks of one document share tiles, which is the paper's
+// composability observation (Section 3.2: throughput depends on the aggregate tokens of a fused call,
+// not on their document of origin) carried below its 128-token shard granularity.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <numeric>
+#include <sstream>
+
+#include "ca_internal.h"
+
+namespace ca {
+
+static thread_local std::string g_err;
+void set_error(const std::string &msg) { g_err = msg; }
+const char *last_error() { return g_err.c_str(); }
+
+namespace {
+struct Fail {
+  int code;
+  std::string msg;
+};
+#define CA_REQUIRE(cond, code, text)        \
+  do {                                      \
+    if (!(cond)) {                          \
+      std::ostringstream os_;               \
+      os_ << text;                          \
+      throw Fail{code, os_.str()};          \
+    }                                       \
+  } while (0)
+
+void validate(const ca_batch_desc *d) {
+  CA_REQUIRE(d != nullptr, CA_ERR_INVALID_ARG, "descriptor is null");
+  CA_REQUIRE(d->n_docs >= 0 && d->n_tasks >= 0, CA_ERR_INVALID_ARG, "negative n_docs or n_tasks");
+  CA_REQUIRE(d->n_q_heads >= 1 && d->n_kv_heads >= 1, CA_ERR_INVALID_ARG, "head counts must be >= 1");
+  CA_REQUIRE(d->n_q_heads % d->n_kv_heads == 0, CA_ERR_UNSUPPORTED,
+             "n_q_heads " << d->n_q_heads << " is not a multiple of n_kv_heads " << d->n_kv_heads);
+  CA_REQUIRE(d->head_dim == 64 || d->head_dim == 128, CA_ERR_UNSUPPORTED,
+             "head_dim " << d->head_dim << " not supported (64 or 128)");
+  CA_REQUIRE(d->total_q >= 0 && d->total_kv >= 0, CA_ERR_INVALID_ARG, "negative total_q or total_kv");
+  const int64_t lim = (int64_t(1) << 31) - 4 * SLOT_ALIGN;
+  CA_REQUIRE(d->total_q < lim && d->total_kv < lim, CA_ERR_UNSUPPORTED, "total_q / total_kv beyond 2^31 rows");
+  CA_REQUIRE(d->total_kv * d->n_kv_heads * d->head_dim < (int64_t(1) << 40), CA_ERR_UNSUPPORTED, "KV buffer too large");
+  if (d->n_docs > 0)
+    CA_REQUIRE(d->doc_kv_start && d->doc_kv_len, CA_ERR_INVALID_ARG, "document arrays are null");
+  if (d->n_tasks > 0) {
+    CA_REQUIRE(d->task_doc && d->task_q_start && d->task_q_len && d->task_q_pos && d->task_kv_len,
+               CA_ERR_INVALID_ARG, "task arrays are null");
+    CA_REQUIRE(d->n_docs > 0, CA_ERR_INVALID_ARG, "tasks given but no documents");
+  }
+  // documents: in bounds, pairwise disjoint KV ranges
+  std::vector<int32_t> order(d->n_docs);
+  std::iota(order.begin(), order.end(), 0);
+  for (int i = 0; i < d->n_docs; ++i) {
+    CA_REQUIRE(d->doc_kv_len[i] >= 1, CA_ERR_INVALID_ARG, "document " << i << " has kv_len " << d->doc_kv_len[i]);
+    CA_REQUIRE(d->doc_kv_start[i] >= 0 && d->doc_kv_start[i] <= d->total_kv - d->doc_kv_len[i], CA_ERR_INVALID_ARG,
+               "document " << i << " KV range [" << d->doc_kv_start[i] << ", +" << d->doc_kv_len[i]
+                           << ") outside the packed KV buffer of " << d->total_kv << " rows");
+  }
+  std::sort(order.begin(), order.end(), [&](int a, int b) { return d->doc_kv_start[a] < d->doc_kv_start[b]; });
+  for (int i = 1; i < d->n_docs; ++i) {
+    int a = order[i - 1], b = order[i];
+    CA_REQUIRE(d->doc_kv_start[a] + d->doc_kv_len[a] <= d->doc_kv_start[b], CA_ERR_INVALID_ARG,
+               "KV ranges of documents " << a << " and " << b << " overlap");
+  }
+  // tasks: in bounds, causal geometry, pairwise disjoint Q ranges
+  std::vector<int32_t> torder(d->n_tasks);
+  std::iota(torder.begin(), torder.end(), 0);
+  for (int t = 0; t < d->n_tasks; ++t) {
+    CA_REQUIRE(d->task_doc[t] >= 0 && d->task_doc[t] < d->n_docs, CA_ERR_INVALID_ARG,
+               "task " << t << " names document " << d->task_doc[t]);
+    CA_REQUIRE(d->task_q_len[t] >= 1, CA_ERR_INVALID_ARG, "task " << t << " has q_len " << d->task_q_len[t]);
+    CA_REQUIRE(d->task_q_start[t] >= 0 && d->task_q_start[t] <= d->total_q - d->task_q_len[t], CA_ERR_INVALID_ARG,
+               "task " << t << " query range outside packed Q of " << d->total_q << " rows");
+    CA_REQUIRE(d->task_q_pos[t] >= 0, CA_ERR_INVALID_ARG, "task " << t << " has negative q_pos");
+    CA_REQUIRE(d->task_q_pos[t] + d->task_q_len[t] <= d->task_kv_len[t], CA_ERR_INVALID_ARG,
+               "task " << t << ": q_pos + q_len = " << d->task_q_pos[t] + d->task_q_len[t] << " exceeds kv_len "
+                       << d->task_kv_len[t] << " (a query row must see itself)");
+    CA_REQUIRE(d->task_kv_len[t] <= d->doc_kv_len[d->task_doc[t]], CA_ERR_INVALID_ARG,
+               "task " << t << ": kv_len " << d->task_kv_len[t] << " exceeds its document's resident KV "
+                       << d->doc_kv_len[d->task_doc[t]]);
+  }
+  std::sort(torder.begin(), torder.end(), [&](int a, int b) { return d->task_q_start[a] < d->task_q_start[b]; });
+  for (int i = 1; i < d->n_tasks; ++i) {
+    int a = torder[i - 1], b = torder[i];
+    CA_REQUIRE(d->task_q_start[a] + d->task_q_len[a] <= d->task_q_start[b], CA_ERR_INVALID_ARG,
+               "query ranges of tasks " << a << " and " << b << " overlap");
+  }
+}
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+void schedule(ca_plan_t *p) {
+  const int hq = p->hq, hkv = p->hkv, g = hq / hkv;
+  // tasks of each document, by position
+  std::vector<std::vector<int32_t>> by_doc(p->n_docs);
+  for (int t = 0; t < p->n_tasks; ++t) by_doc[p->task_doc[t]].push_back(t);
+  int64_t padded = 0;
+  for (auto &v : by_doc) {
+    int64_t n = 0;
+    for (int t : v) n += p->task_q_len[t];
+    padded += round_up(n, SLOT_ALIGN);
+  }
+  CA_REQUIRE(padded < (int64_t(1) << 31) - SLOT_ALIGN, CA_ERR_UNSUPPORTED, "too many padded query rows");
+  p->slot_row.assign(padded, -1);
+  p->slot_pos.assign(padded, 0);
+
+  struct TileRef {
+    int32_t cost;
+    FwdUnit u;
+  };
+  std::vector<TileRef> ftiles;
+  std::vector<BwdUnit> btiles;
+  int64_t s = 0;
+  for (int dd = 0; dd < p->n_docs; ++dd) {
+    auto &v = by_doc[dd];
+    if (v.empty()) continue;
+    std::stable_sort(v.begin(), v.end(), [&](int a, int b) { return p->task_q_pos[a] < p->task_q_pos[b]; });
+    // overlapping position ranges of two tasks would interleave; a merge by position keeps slots sorted
+    struct Row {
+      int32_t pos, row;
+    };
+    const int64_t s0 = s;
+    bool sorted = true;
+    for (size_t i = 1; i < v.size(); ++i)
+      if (p->task_q_pos[v[i]] < p->task_q_pos[v[i - 1]] + p->task_q_len[v[i - 1]]) sorted = false;
+    for (int t : v)
+      for (int64_t i = 0; i < p->task_q_len[t]; ++i, ++s) {
+        p->slot_row[s] = int32_t(p->task_q_start[t] + i);
+        p->slot_pos[s] = int32_t(p->task_q_pos[t] + i);
+      }
+    if (!sorted) {  // rare: tasks of one document covering the same positions twice
+      std::vector<Row> rows(s - s0);
+      for (int64_t i = s0; i < s; ++i) rows[i - s0] = {p->slot_pos[i], p->slot_row[i]};
+      std::stable_sort(rows.begin(), rows.end(), [](const Row &a, const Row &b) { return a.pos < b.pos; });
+      for (int64_t i = s0; i < s; ++i) p->slot_pos[i] = rows[i - s0].pos, p->slot_row[i] = rows[i - s0].row;
+    }
+    const int32_t last_pos = p->slot_pos[s - 1];
+    const int64_t s1 = round_up(s, SLOT_ALIGN);
+    for (; s < s1; ++s) p->slot_pos[s] = last_pos;  // padding slots: row -1, position of the last real row
+    const int32_t kv_row0 = int32_t(p->doc_kv_start[dd]);
+    // forward tiles
+    for (int64_t a = s0; a < s1; a += FWD_BM) {
+      if (p->slot_row[a] < 0) break;  // tile of pure padding
+      int32_t n_keys = p->slot_pos[a + FWD_BM - 1] + 1;
+      ftiles.push_back({(n_keys + FWD_BN - 1) / FWD_BN, {int32_t(a), kv_row0, n_keys, 0}});
+    }
+    // backward KV tiles: keys 0 .. last_pos of the document
+    const int32_t cover = last_pos + 1;
+    for (int32_t k0 = 0; k0 < cover; k0 += BWD_BN) {
+      // first slot whose position can see key k0
+      const int32_t *b = p->slot_pos.data() + s0, *e = p->slot_pos.data() + s1;
+      int64_t first = std::lower_bound(b, e, k0) - b;
+      first = first / BWD_BQ * BWD_BQ;
+      int64_t end = s1;
+      while (end - BWD_BQ >= s0 + first && p->slot_row[end - BWD_BQ] < 0) end -= BWD_BQ;  // drop pure-padding blocks
+      BwdUnit u{int32_t(s0 + first), int32_t(end), kv_row0 + k0, std::min<int32_t>(BWD_BN, cover - k0), k0, 0};
+      btiles.push_back(u);
+    }
+  }
+  // longest first (the hardware dispatcher hands out workgroups in index order, so this is LPT
+  // list scheduling); unit index modulo n_kv_heads equals the KV head, so that with workgroups dealt
+  // round-robin to the 8 XCDs each L2 sees the K/V of as few KV heads as possible.
+  std::stable_sort(ftiles.begin(), ftiles.end(), [](const TileRef &a, const TileRef &b) { return a.cost > b.cost; });
+  p->fwd_units.reserve(ftiles.size() * hq);
+  p->fwd_steps = 0;
+  for (auto &t : ftiles)
+    for (int i = 0; i < hq; ++i) {
+      FwdUnit u = t.u;
+      u.head = (i % hkv) * g + i / hkv;
+      p->fwd_units.push_back(u);
+      p->fwd_steps += t.cost;
+    }
+  std::stable_sort(btiles.begin(), btiles.end(), [](const BwdUnit &a, const BwdUnit &b) {
+    return (a.slot_end - a.slot_begin) > (b.slot_end - b.slot_begin);
+  });
+  p->bwd_units.reserve(btiles.size() * hkv);
+  p->bwd_steps = 0;
+  for (auto &t : btiles)
+    for (int h = 0; h < hkv; ++h) {
+      BwdUnit u = t;
+      u.kv_head = h;
+      p->bwd_units.push_back(u);
+      p->bwd_steps += int64_t(u.slot_end - u.slot_begin) / BWD_BQ * g;
+    }
+  // workspace: backward needs the fp32 dQ accumulator and Delta
+  const size_t dq_bytes = size_t(p->total_q) * hq * p->d * sizeof(float);
+  p->ws_off_delta = (dq_bytes + 255) / 256 * 256;
+  p->ws_bwd = p->ws_off_delta + (size_t(p->total_q) * hq * sizeof(float) + 255) / 256 * 256;
+  p->ws_fwd = 0;
+}
+}  // namespace
+
+int build_plan(const ca_batch_desc *desc, ca_plan_t **out) {
+  if (!out) {
+    set_error("output plan pointer is null");
+    return CA_ERR_INVALID_ARG;
+  }
+  *out = nullptr;
+  ca_plan_t *p = nullptr;
+  try {
+    validate(desc);
+    p = new ca_plan_t();
+    p->n_docs = desc->n_docs, p->n_tasks = desc->n_tasks;
+    p->hq = desc->n_q_heads, p->hkv = desc->n_kv_heads, p->d = desc->head_dim;
+    p->total_q = desc->total_q, p->total_kv = desc->total_kv;
+    p->scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / std::sqrt(float(desc->head_dim));
+    if (desc->n_docs > 0) {
+      p->doc_kv_start.assign(desc->doc_kv_start, desc->doc_kv_start + desc->n_docs);
+      p->doc_kv_len.assign(desc->doc_kv_len, desc->doc_kv_len + desc->n_docs);
+    }
+    if (desc->n_tasks > 0) {
+      p->task_doc.assign(desc->task_doc, desc->task_doc + desc->n_tasks);
+      p->task_q_start.assign(desc->task_q_start, desc->task_q_start + desc->n_tasks);
+      p->task_q_len.assign(desc->task_q_len, desc->task_q_len + desc->n_tasks);
+      p->task_q_pos.assign(desc->task_q_pos, desc->task_q_pos + desc->n_tasks);
+      p->task_kv_len.assign(desc->task_kv_len, desc->task_kv_len + desc->n_tasks);
+    }
+    schedule(p);
+  } catch (const Fail &f) {
+    delete p;
+    set_error(f.msg);
+    return f.code;
+  } catch (const std::bad_alloc &) {
+    delete p;
+    set_error("out of host memory while planning");
+    return CA_ERR_INVALID_ARG;
+  }
+  *out = p;
+  return CA_OK;
+}
+
+}  // namespace ca
+
+extern "C" {
+
+int ca_plan_host(const ca_batch_desc *desc, ca_plan_t **out) { return ca::build_plan(desc, out); }
+
+const char *ca_last_error(void) { return ca::last_error(); }
+
+const char *ca_error_string(int code) {
+  switch (code) {
+    case CA_OK: return "ok";
+    case CA_ERR_INVALID_ARG: return "invalid argument";
+    case CA_ERR_UNSUPPORTED: return "unsupported configuration";
+    case CA_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
+    case CA_ERR_HIP: return "HIP runtime error";
+    case CA_ERR_STATE: return "plan not uploaded to this device";
+    default: return "unknown error code";
+  }
+}
+
+int ca_plan_workspace_bytes(const ca_plan_t *p, size_t *fwd, size_t *bwd) {
+  if (!p) {
+    ca::set_error("plan is null");
+    return CA_ERR_INVALID_ARG;
+  }
+  if (fwd) *fwd = p->ws_fwd;
+  if (bwd) *bwd = p->ws_bwd;
+  return CA_OK;
+}
+
+int ca_plan_info(const ca_plan_t *p, int64_t *out, int n) {
+  if (!p) return 0;
+  const int64_t v[10] = {ca::FWD_BM, int64_t(p->fwd_units.size() / (p->hq ? p->hq : 1)), int64_t(p->fwd_units.size()),
+                         ca::BWD_BN, int64_t(p->bwd_units.size()), ca::FWD_BN, int64_t(p->slot_row.size()),
+                         p->fwd_steps, p->bwd_steps, ca::BWD_BQ};
+  for (int i = 0; i < n && i < 10 && out; ++i) out[i] = v[i];
+  return 10;
+}
+
+int64_t ca_plan_rows(const ca_plan_t *p, int32_t *rows, int32_t *pos) {
+  if (!p) return 0;
+  if (rows) std::memcpy(rows, p->slot_row.data(), p->slot_row.size() * sizeof(int32_t));
+  if (pos) std::memcpy(pos, p->slot_pos.data(), p->slot_pos.size() * sizeof(int32_t));
+  return int64_t(p->slot_row.size());
+}
+
+int64_t ca_plan_fwd_units(const ca_plan_t *p, int32_t *units) {
+  if (!p) return 0;
+  if (units) std::memcpy(units, p->fwd_units.data(), p->fwd_units.size() * sizeof(ca::FwdUnit));
+  return int64_t(p->fwd_units.size());
+}
+
+int64_t ca_plan_bwd_units(const ca_plan_t *p, int32_t *units) {
+  if (!p) return 0;
+  if (units) std::memcpy(units, p->bwd_units.data(), p->bwd_units.size() * sizeof(ca::BwdUnit));
+  return int64_t(p->bwd_units.size());
+}
+
+}  // extern "C"
