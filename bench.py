@@ -1,0 +1,135 @@
+#!/usr/bin/env python3
+"""Benchmark of the attention-server hot path on one MI355X.
+
+A step is one pass of the whole path - ca_forward then ca_backward through the C ABI - over one fused
+batch of CA-tasks with all inputs already resident in HBM.  The reported value is causal-FLOP
+throughput, 14 * head_dim * n_q_heads * (visible query-key pairs) flops per step (2 contractions
+forward, 5 backward).  Planning (ca_plan) and allocation are outside the timed region and reported
+separately.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
+
+
+def cpu_baseline(index: int):
+    """The fp64 oracle, as it stands, timed on this host's cores on a bounded sample of the workload:
+    the generator's token-count/16 twin restricted to one KV head's query-head group."""
+    import numpy as np
+    import oracle
+    from paper_2510_18121_amd import workloads as W
+
+    b = W.config(index, 1 if index == 1 else 16)
+    if index != 1:
+        b = W.one_kv_group(b)
+    if index == 4:
+        b = W.one_kv_group(W.config(4, 64))
+    q, k, v, d_o = W.make_tensors(b, "cpu")
+    f64 = lambda t: t.float().numpy().astype(np.float64)
+    q, k, v, d_o = f64(q), f64(k), f64(v), f64(d_o)
+    t0 = time.perf_counter()
+    oracle.forward_backward(b, q, k, v, d_o)
+    dt = time.perf_counter() - t0
+    return {"value": b.flops()["total"] / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{b.name}: {b.total_q} tokens, {b.n_q_heads}/{b.n_kv_heads} heads, "
+                      f"{b.flops()['total']:.3e} causal flops in {dt:.1f} s (fp64)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", type=int, default=3, help="1..5; 3 is the 8B-class 128K-token workload")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported "
+                 "(no collectives or sharding are part of it)")
+
+    import torch
+    from paper_2510_18121_amd import binding as B
+    from paper_2510_18121_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    props = torch.cuda.get_device_properties(dev)
+
+    b = W.config(args.workload)
+    fl = b.flops()
+    q, k, v, d_o = W.make_tensors(b, dev)
+    t0 = time.perf_counter()
+    plan = B.ca_plan(b)
+    torch.cuda.synchronize()
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    ws = B.alloc_workspace(plan, dev)
+    o = torch.empty_like(q)
+    lse = torch.empty((b.n_q_heads, b.total_q), dtype=torch.float32, device=dev)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+
+    def step():
+        B.ca_forward(plan, q, k, v, o, lse, ws)
+        B.ca_backward(plan, q, k, v, o, d_o, lse, dq, dk, dv, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    plan.profile_enable(True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    wall0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    # per-kernel durations: HIP events recorded by the library on the launch stream, one more pass
+    kern = {"fwd_kernel_ms": [], "bwd_prep_ms": [], "bwd_dkv_ms": [], "bwd_dq_ms": []}
+    for _ in range(max(1, min(args.steps, 3))):
+        step()
+        r = plan.profile_read()
+        for kk in kern:
+            kern[kk].append(r[kk])
+    kavg = {kk: sum(vv) / len(vv) for kk, vv in kern.items()}
+    plan.profile_enable(False)
+
+    tflops = fl["total"] / (ms_per_step * 1e-3) / 1e12
+    # the dK/dV kernel executes 4 of the backward's contractions (S, dP, dV, dK): 8*D*Hq*pairs flops
+    dkv_flops = fl["bwd"] * 0.8
+    bwd_main_tflops = dkv_flops / (kavg["bwd_dkv_ms"] * 1e-3) / 1e12 if kavg["bwd_dkv_ms"] > 0 else 0.0
+    fwd_tflops = fl["fwd"] / (kavg["fwd_kernel_ms"] * 1e-3) / 1e12 if kavg["fwd_kernel_ms"] > 0 else 0.0
+    out = {
+        "metric": "core-attention fwd+bwd TFLOP/s (causal FLOPs), 1 GPU",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": b.name, "tokens": b.total_q, "n_q_heads": b.n_q_heads, "n_kv_heads": b.n_kv_heads,
+                   "head_dim": b.head_dim, "docs": b.n_docs, "ca_tasks": b.n_tasks, "pairs": fl["pairs"],
+                   "flops_fwd_bwd": fl["total"]},
+        "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
+        "device": {"name": props.name, "cus": props.multi_processor_count,
+                   "clock_mhz": getattr(props, "clock_rate", 0) / 1e3},
+        "kernels_ms": kavg, "fwd_kernel_tflops": fwd_tflops, "plan_ms": plan_ms, "wall_s_timed": wall,
+        "roofline": {"kernel": "ca_bwd_dkv_kernel", "bound": "mfma", "achieved": bwd_main_tflops,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": bwd_main_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

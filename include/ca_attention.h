@@ -95,14 +95,26 @@ int ca_forward(const ca_plan_t *plan, const void *q, const void *k, const void *
 /*
  * ca_backward: dQ, dK, dV of L = sum(dO * O) given the forward's inputs and its saved O and LSE
  * (nothing else is kept between the two calls).  dq like q; dk, dv like k, v (every row written).
- * ws: device workspace of at least bwd_bytes, 256-byte aligned.  dQ is accumulated with floating-point
- * atomics, so its low-order bits may differ from run to run.  Allocates nothing, never synchronises.
+ * ws: device workspace of at least bwd_bytes, 256-byte aligned.  No atomics are used: results are
+ * bit-reproducible from run to run.  Allocates nothing, never synchronises.
  */
 int ca_backward(const ca_plan_t *plan, const void *q, const void *k, const void *v, const void *o,
                 const void *d_o, const float *lse, void *dq, void *dk, void *dv,
                 void *ws, size_t ws_bytes, void *hip_stream);
 
 void ca_plan_destroy(ca_plan_t *plan);
+
+/*
+ * Per-kernel timing for profilers and cost models (Section 4.2's profiler benchmarks core attention over
+ * a grid of shapes; this is the hook it reads).  After ca_profile_enable(plan, 1) every ca_forward /
+ * ca_backward on that plan records HIP events on the caller's stream around its kernels.
+ * ca_profile_read blocks until the last recorded events have completed and writes milliseconds to
+ * out[0..4): {forward kernel, backward preparation (Delta and log-sum-exp in slot order, zero fills
+ * when some rows belong to no task), backward dK/dV kernel, backward dQ kernel}; entries of calls not made since enabling are 0.  Enabling creates events
+ * (the only allocation); disabling destroys them.
+ */
+int ca_profile_enable(ca_plan_t *plan, int on);
+int ca_profile_read(ca_plan_t *plan, float *out_ms);
 
 const char *ca_error_string(int code);
 const char *ca_last_error(void); /* thread-local detail of the last failing call on this thread */

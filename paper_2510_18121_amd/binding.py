@@ -57,6 +57,8 @@ def lib() -> ctypes.CDLL:
         L.ca_error_string.argtypes = [ctypes.c_int]
         L.ca_error_string.restype = ctypes.c_char_p
         L.ca_last_error.restype = ctypes.c_char_p
+        L.ca_profile_enable.argtypes = [vp, ctypes.c_int]
+        L.ca_profile_read.argtypes = [vp, vp]
         L.ca_plan_info.argtypes = [vp, vp, ctypes.c_int]
         for f in (L.ca_plan_rows, L.ca_plan_fwd_units, L.ca_plan_bwd_units):
             f.restype = ctypes.c_int64
@@ -134,6 +136,14 @@ class Plan:
         u = np.zeros((n, 6), np.int32)
         lib().ca_plan_bwd_units(self.handle, u.ctypes.data)
         return u
+
+    def profile_enable(self, on=True):
+        _check(lib().ca_profile_enable(self.handle, 1 if on else 0))
+
+    def profile_read(self) -> dict:
+        out = np.zeros(4, np.float32)
+        _check(lib().ca_profile_read(self.handle, out.ctypes.data))
+        return dict(zip(("fwd_kernel_ms", "bwd_prep_ms", "bwd_dkv_ms", "bwd_dq_ms"), out.tolist()))
 
     def destroy(self):
         if self.handle:

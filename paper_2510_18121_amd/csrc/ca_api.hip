@@ -9,7 +9,7 @@ namespace ca {
 hipError_t launch_fwd(const ca_plan_t *p, const void *q, const void *k, const void *v, void *o, float *lse,
                       hipStream_t st);
 hipError_t launch_bwd(const ca_plan_t *p, const void *q, const void *k, const void *v, const void *o, const void *d_o,
-                      const float *lse, void *dq, void *dk, void *dv, void *ws, hipStream_t st);
+                      const float *lse, void *dq, void *dk, void *dv, void *ws, hipStream_t st, hipEvent_t *ev);
 
 static int hip_fail(const char *what, hipError_t e) {
   std::ostringstream os;
@@ -111,8 +111,56 @@ int ca_plan(const ca_batch_desc *desc, ca_plan_t **out) {
   return rc;
 }
 
+int ca_profile_enable(ca_plan_t *p, int on) {
+  using namespace ca;
+  if (!p) {
+    set_error("plan is null");
+    return CA_ERR_INVALID_ARG;
+  }
+  if (on && !p->profile) {
+    for (int i = 0; i < 6; ++i) {
+      hipEvent_t e;
+      CA_HIP(hipEventCreate(&e));
+      p->ev[i] = e;
+    }
+    p->profile = true;
+  } else if (!on && p->profile) {
+    for (int i = 0; i < 6; ++i)
+      if (p->ev[i]) (void)hipEventDestroy(static_cast<hipEvent_t>(p->ev[i])), p->ev[i] = nullptr;
+    p->profile = false;
+  }
+  p->ev_fwd = p->ev_bwd = false;
+  return CA_OK;
+}
+
+int ca_profile_read(ca_plan_t *p, float *out) {
+  using namespace ca;
+  if (!p || !out) {
+    set_error("plan or output is null");
+    return CA_ERR_INVALID_ARG;
+  }
+  for (int i = 0; i < 4; ++i) out[i] = 0.f;
+  if (!p->profile) {
+    set_error("profiling is not enabled on this plan");
+    return CA_ERR_STATE;
+  }
+  auto E = [&](int i) { return static_cast<hipEvent_t>(p->ev[i]); };
+  if (p->ev_fwd) {
+    CA_HIP(hipEventSynchronize(E(1)));
+    CA_HIP(hipEventElapsedTime(&out[0], E(0), E(1)));
+  }
+  if (p->ev_bwd) {
+    CA_HIP(hipEventSynchronize(E(5)));
+    CA_HIP(hipEventElapsedTime(&out[1], E(2), E(3)));
+    CA_HIP(hipEventElapsedTime(&out[2], E(3), E(4)));
+    CA_HIP(hipEventElapsedTime(&out[3], E(4), E(5)));
+  }
+  return CA_OK;
+}
+
 void ca_plan_destroy(ca_plan_t *p) {
   if (!p) return;
+  if (p->profile) (void)ca_profile_enable(p, 0);
   ca::free_device(p);
   delete p;
 }
@@ -130,8 +178,15 @@ int ca_forward(const ca_plan_t *p, const void *q, const void *k, const void *v, 
     set_error("k or v is null");
     return CA_ERR_INVALID_ARG;
   }
-  hipError_t e = launch_fwd(p, q, k, v, o, lse, static_cast<hipStream_t>(hip_stream));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  ca_plan_t *mp = const_cast<ca_plan_t *>(p);  // timing state only
+  if (p->profile) (void)hipEventRecord(static_cast<hipEvent_t>(mp->ev[0]), st);
+  hipError_t e = launch_fwd(p, q, k, v, o, lse, st);
   if (e != hipSuccess) return hip_fail("forward launch", e);
+  if (p->profile) {
+    (void)hipEventRecord(static_cast<hipEvent_t>(mp->ev[1]), st);
+    mp->ev_fwd = true;
+  }
   return CA_OK;
 }
 
@@ -148,8 +203,11 @@ int ca_backward(const ca_plan_t *p, const void *q, const void *k, const void *v,
     set_error("k, v, dk or dv is null");
     return CA_ERR_INVALID_ARG;
   }
-  hipError_t e = launch_bwd(p, q, k, v, o, d_o, lse, dq, dk, dv, ws, static_cast<hipStream_t>(hip_stream));
+  ca_plan_t *mp = const_cast<ca_plan_t *>(p);  // timing state only
+  hipError_t e = launch_bwd(p, q, k, v, o, d_o, lse, dq, dk, dv, ws, static_cast<hipStream_t>(hip_stream),
+                            p->profile ? reinterpret_cast<hipEvent_t *>(&mp->ev[2]) : nullptr);
   if (e != hipSuccess) return hip_fail("backward launch", e);
+  if (p->profile) mp->ev_bwd = true;
   return CA_OK;
 }
 

@@ -59,3 +59,80 @@ __device__ __forceinline__ int wave_min(int v) {
 }
 
 }  // namespace ca
+
+// ---------------------------------------------------------------------------------------------
+// LDS tiles of R rows x D bf16 in natural (row-major) layout, rows unpadded, with the 16-byte chunks of
+// each row XOR-swizzled by a function of the row.  gfx950's LDS has 64 banks of 4 bytes (256 B/clk).
+//   * a 16-byte read (lane <-> row, all lanes the same logical chunk) is served 16 consecutive rows
+//     at a time, so sw(r) must take 16 (D=128) distinct values over 16 consecutive rows
+//     (for D=64, where two rows share a 256-byte line, 8 distinct values over rows of equal parity);
+//   * an 8-byte transposing read is served 4 consecutive rows x two adjacent 32-byte pieces at a time, so
+//     bits 2..3 of sw must follow the row's low bits.
+// sw(r) below satisfies both, so one tile can feed natural and transposed MFMA operands.
+// Because rows are unpadded, a tile can be filled by global_load_lds_dwordx4, which writes
+// lane i's 16 bytes at (wave-uniform LDS base) + 16 i: the swizzle is applied by choosing which global
+// chunk each lane fetches.
+namespace ca {
+
+template <int D>
+__device__ __forceinline__ int tile_sw(int r) {
+  return D == 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
+}
+
+// byte offset of logical 16-byte chunk c of row r
+template <int D>
+__device__ __forceinline__ int tile_off(int r, int c) {
+  return r * (2 * D) + ((c ^ tile_sw<D>(r)) << 4);
+}
+
+#define CA_GLOBAL __attribute__((address_space(1)))
+#define CA_CONST __attribute__((address_space(4)))
+
+// One wave-wide direct load global -> LDS: lane i's 16 (or 4) bytes from `src` land at
+// lds_base + 16 i (or 4 i); lds_base must be wave-uniform.  Written as inline assembly on purpose: the
+// compiler's wait-count insertion treats every LDS read as possibly aliasing an in-flight direct load
+// and would drain the whole prefetch queue (s_waitcnt vmcnt(0)) before it.  Here the kernels pace
+// the queue themselves with wait_vmcnt<N>() and a barrier.  Loads the compiler does not know about can
+// only make its own vmcnt waits stricter than needed, never weaker: vector loads retire in order.
+__device__ __forceinline__ void load_lds16(const void *src, char *lds_base_uniform) {
+  const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(CA_LDS char *)lds_base_uniform);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(src), "s"(base)
+               : "memory", "m0");
+}
+__device__ __forceinline__ void load_lds4(const void *src, char *lds_base_uniform) {
+  const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(CA_LDS char *)lds_base_uniform);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+               :
+               : "v"(src), "s"(base)
+               : "memory", "m0");
+}
+
+// workgroup barrier without the memory fence of __syncthreads() (which would also drain the direct loads):
+// the caller has waited for its own LDS reads (lgkmcnt) and for the direct loads that must be visible
+__device__ __forceinline__ void barrier_nofence() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Pins a loaded register value: the load is issued and waited for before this point (the compiler would
+// otherwise be free to sink loads from read-only memory to their first use inside a loop, together
+// with a vector-memory wait that would drain the direct-load queue on every iteration).
+__device__ __forceinline__ void pin(bf16x8 &v) {
+  u32x4 w = __builtin_bit_cast(u32x4, v);
+  asm volatile("" : "+v"(w));
+  v = __builtin_bit_cast(bf16x8, w);
+}
+__device__ __forceinline__ void pin(float &v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void pin(int &v) { asm volatile("" : "+v"(v)); }
+
+// wait until at most n of this wave's vector-memory loads are outstanding (n <= 63)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  // the empty asm statements keep the compiler from moving loads or stores across the wait
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+  asm volatile("" ::: "memory");
+}
+
+}  // namespace ca

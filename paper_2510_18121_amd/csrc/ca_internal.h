@@ -11,8 +11,8 @@ namespace ca {
 
 // Tile geometry.  Every document's sorted query rows occupy a run of "slots" padded to SLOT_ALIGN, so
 // that forward tiles (FWD_BM slots) and backward q blocks (BWD_BQ slots) both tile the same arrays.
-constexpr int SLOT_ALIGN = 128;
-constexpr int FWD_BM = 128;  // query rows per forward work unit (4 waves x 32)
+constexpr int SLOT_ALIGN = 256;
+constexpr int FWD_BM = 256;  // query rows per forward work unit (8 waves x 32)
 constexpr int FWD_BN = 64;   // keys per forward inner step
 constexpr int BWD_BN = 128;  // keys owned by one backward work unit (4 waves x 32)
 constexpr int BWD_BQ = 64;   // query rows per backward inner step
@@ -47,13 +47,18 @@ struct ca_plan {
   std::vector<ca::FwdUnit> fwd_units;
   std::vector<ca::BwdUnit> bwd_units;
   int64_t fwd_steps = 0, bwd_steps = 0;
-  // workspace layout for backward: [dq_acc fp32 total_q*hq*d][delta fp32 hq*total_q]
-  size_t ws_fwd = 0, ws_bwd = 0, ws_off_delta = 0;
+  // workspace layout for backward: [Delta fp32 hq*padded_slots][log2e*LSE fp32 hq*padded_slots]
+  size_t ws_fwd = 0, ws_bwd = 0, ws_off_l2 = 0;
+  bool q_covered = false, kv_covered = false;  // every packed Q row / KV row belongs to some unit
   // device copies
   int device = -1;
   int32_t *d_slot_row = nullptr, *d_slot_pos = nullptr;
   ca::FwdUnit *d_fwd_units = nullptr;
   ca::BwdUnit *d_bwd_units = nullptr;
+  // optional timing events (hipEvent_t, kept as void* so that host-only code needs no HIP header)
+  bool profile = false;
+  void *ev[7] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  bool ev_fwd = false, ev_bwd = false;
 };
 
 namespace ca {

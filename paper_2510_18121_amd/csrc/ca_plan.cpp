@@ -116,7 +116,8 @@ void schedule(ca_plan_t *p) {
   };
   std::vector<TileRef> ftiles;
   std::vector<BwdUnit> btiles;
-  int64_t s = 0;
+  int64_t s = 0, covered_kv = 0, covered_q = 0;
+  for (int t = 0; t < p->n_tasks; ++t) covered_q += p->task_q_len[t];
   for (int dd = 0; dd < p->n_docs; ++dd) {
     auto &v = by_doc[dd];
     if (v.empty()) continue;
@@ -150,18 +151,25 @@ void schedule(ca_plan_t *p) {
       int32_t n_keys = p->slot_pos[a + FWD_BM - 1] + 1;
       ftiles.push_back({(n_keys + FWD_BN - 1) / FWD_BN, {int32_t(a), kv_row0, n_keys, 0}});
     }
-    // backward KV tiles: keys 0 .. last_pos of the document
+    // backward KV tiles: every resident key of the document.  Keys beyond the last query position get a
+    // unit without query blocks, which writes their zero gradient.
     const int32_t cover = last_pos + 1;
-    for (int32_t k0 = 0; k0 < cover; k0 += BWD_BN) {
-      // first slot whose position can see key k0
-      const int32_t *b = p->slot_pos.data() + s0, *e = p->slot_pos.data() + s1;
-      int64_t first = std::lower_bound(b, e, k0) - b;
-      first = first / BWD_BQ * BWD_BQ;
-      int64_t end = s1;
-      while (end - BWD_BQ >= s0 + first && p->slot_row[end - BWD_BQ] < 0) end -= BWD_BQ;  // drop pure-padding blocks
-      BwdUnit u{int32_t(s0 + first), int32_t(end), kv_row0 + k0, std::min<int32_t>(BWD_BN, cover - k0), k0, 0};
+    const int32_t doc_len = int32_t(p->doc_kv_len[dd]);
+    for (int32_t k0 = 0; k0 < doc_len; k0 += BWD_BN) {
+      BwdUnit u{int32_t(s1), int32_t(s1), kv_row0 + k0, std::min<int32_t>(BWD_BN, doc_len - k0), k0, 0};
+      if (k0 < cover) {
+        // first slot whose position can see key k0
+        const int32_t *b = p->slot_pos.data() + s0, *e = p->slot_pos.data() + s1;
+        int64_t first = std::lower_bound(b, e, k0) - b;
+        first = first / BWD_BQ * BWD_BQ;
+        int64_t end = s1;
+        while (end - BWD_BQ >= s0 + first && p->slot_row[end - BWD_BQ] < 0) end -= BWD_BQ;  // drop pure-padding blocks
+        u.slot_begin = int32_t(s0 + first);
+        u.slot_end = int32_t(end);
+      }
       btiles.push_back(u);
     }
+    covered_kv += doc_len;
   }
   // longest first (the hardware dispatcher hands out workgroups in index order, so this is LPT
   // list scheduling); unit index modulo n_kv_heads equals the KV head, so that with workgroups dealt
@@ -188,10 +196,12 @@ void schedule(ca_plan_t *p) {
       p->bwd_units.push_back(u);
       p->bwd_steps += int64_t(u.slot_end - u.slot_begin) / BWD_BQ * g;
     }
-  // workspace: backward needs the fp32 dQ accumulator and Delta
-  const size_t dq_bytes = size_t(p->total_q) * hq * p->d * sizeof(float);
-  p->ws_off_delta = (dq_bytes + 255) / 256 * 256;
-  p->ws_bwd = p->ws_off_delta + (size_t(p->total_q) * hq * sizeof(float) + 255) / 256 * 256;
+  p->q_covered = covered_q == p->total_q;
+  p->kv_covered = covered_kv == p->total_kv;
+  // workspace of backward: per (head, slot) fp32 Delta and log2(e)*LSE, in slot order
+  const size_t per = (size_t(padded) * hq * sizeof(float) + 255) / 256 * 256;
+  p->ws_off_l2 = per;
+  p->ws_bwd = 2 * per;
   p->ws_fwd = 0;
 }
 }  // namespace
