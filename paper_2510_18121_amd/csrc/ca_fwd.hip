@@ -196,6 +196,36 @@ __global__ __launch_bounds__(512, 2) void ca_fwd_kernel(const FwdUnit *__restric
         acc[b] = mfma32(a, pb[kt], acc[b]);
       }
     }
+    // The first rows of a document see a handful of keys, their output is as large as a single V row, and
+    // the 2^-9 relative rounding of P to bf16 then shows up at the 1e-2 level next to the output's own bf16
+    // rounding.  For the waves that hold such rows, the rounding residue of P is fed through the matrix pipe
+    // as a second bf16 operand (P = hi + lo), which makes P V as good as fp32 at negligible cost: it
+    // happens only in the first tile of the first query rows of each document.
+    if (j == 0 && wmin < FWD_BN) {
+      bf16x8 pl[4];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        uint32_t l0[4], l1[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t h0 = __builtin_bit_cast(u32x4, pb[t])[e], h1 = __builtin_bit_cast(u32x4, pb[2 + t])[e];
+          l0[e] = pack_bf16(s0[8 * t + 2 * e] - __uint_as_float(h0 << 16),
+                            s0[8 * t + 2 * e + 1] - __uint_as_float(h0 & 0xffff0000u));
+          l1[e] = pack_bf16(s1[8 * t + 2 * e] - __uint_as_float(h1 << 16),
+                            s1[8 * t + 2 * e + 1] - __uint_as_float(h1 & 0xffff0000u));
+        }
+        pl[t] = __builtin_bit_cast(bf16x8, u32x4{l0[0], l0[1], l0[2], l0[3]});
+        pl[2 + t] = __builtin_bit_cast(bf16x8, u32x4{l1[0], l1[1], l1[2], l1[3]});
+      }
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt) {
+#pragma unroll
+        for (int b = 0; b < NDB; ++b) {
+          bf16x8 a = join(lds_read_tr4(vt + voff[0][b] + 16 * kt * ROWB), lds_read_tr4(vt + voff[1][b] + 16 * kt * ROWB));
+          acc[b] = mfma32(a, pl[kt], acc[b]);
+        }
+      }
+    }
   };
 
   for (int j = 0; j < n_tiles; ++j) {

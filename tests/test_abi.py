@@ -1,0 +1,43 @@
+"""The C-ABI library loads without a GPU and exports every function include/ca_attention.h declares."""
+import ctypes
+import os
+import re
+
+from paper_2510_18121_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "ca_attention.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    names = re.findall(r"\b(ca_[a-z_0-9]+)\s*\(", src)
+    return sorted(set(names))
+
+
+def test_header_functions_are_exported():
+    names = declared_functions()
+    assert {"ca_plan", "ca_plan_host", "ca_plan_upload", "ca_forward", "ca_backward", "ca_plan_destroy",
+            "ca_plan_workspace_bytes", "ca_error_string", "ca_last_error", "ca_profile_enable",
+            "ca_profile_read", "ca_plan_info", "ca_plan_rows", "ca_plan_fwd_units", "ca_plan_bwd_units"} <= set(names)
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_error_strings():
+    lib = B.lib()
+    seen = set()
+    for code in (0, -1, -2, -3, -4, -5):
+        s = lib.ca_error_string(code).decode()
+        assert s and s not in seen
+        seen.add(s)
+    assert "unknown" in lib.ca_error_string(-99).decode()
+
+
+def test_calls_without_plan_fail_cleanly():
+    lib = B.lib()
+    assert lib.ca_forward(None, None, None, None, None, None, None, 0, None) == B.CA_ERR_INVALID_ARG
+    assert lib.ca_plan_workspace_bytes(None, None, None) == B.CA_ERR_INVALID_ARG
+    assert lib.ca_plan_host(None, None) == B.CA_ERR_INVALID_ARG
+    lib.ca_plan_destroy(None)  # no-op

@@ -1,0 +1,181 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the same bf16 bits.
+Tolerances: max |O - O_ref| <= 1e-2, relative L2 <= 1e-2 on dQ, dK, dV, max |LSE - LSE_ref| <= 2e-3."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import parity_util as P
+from paper_2510_18121_amd import binding as B
+from paper_2510_18121_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def full_check(b, tag, rows=None):
+    q, k, v, d_o = W.make_tensors(b, DEV)
+    hip = P.run_hip(b, q, k, v, d_o)
+    ref = P.run_oracle(b, q, k, v, d_o)
+    e = P.errors(hip, ref, rows)
+    print(tag, e, flush=True)
+    P.assert_parity(e, tag)
+    return hip, ref, (q, k, v, d_o)
+
+
+def test_tiny_workload_full_tensors():
+    full_check(W.config(1), "cfg1")
+
+
+@pytest.mark.parametrize("idx,div", [(2, 16), (3, 16), (4, 64), (5, 16)])
+def test_downscaled_twins_full_tensors(idx, div):
+    """Same generators as the full workloads, token counts divided, one KV head with its query-head group."""
+    full_check(W.one_kv_group(W.config(idx, div)), f"cfg{idx}/{div}")
+
+
+RAGGED = [1, 2, 15, 17, 31, 33, 63, 65, 127, 129, 255, 257, 300]
+
+
+@pytest.mark.parametrize("d,hq,hkv", [(64, 4, 2), (128, 4, 4), (128, 8, 1)])
+def test_ragged_shards_and_head_layouts(d, hq, hkv):
+    """One document cut at ragged points (1-row shards included), shards shuffled in packed Q, next to a
+    one-token document and a document cut in two; MHA, GQA 2 and GQA 8."""
+    tasks, a = [], 0
+    for n in RAGGED:
+        tasks.append((0, a, n))
+        a += n
+    docs = [a, 1, 200]
+    tasks += [(1, 0, 1), (2, 0, 77), (2, 77, 123)]
+    order = list(np.random.default_rng(11).permutation(len(tasks)))
+    b = W.custom(docs, tasks, hq, hkv, d, doc_order=[2, 0, 1], task_order=order, seed=21)
+    full_check(b, f"ragged d{d} {hq}/{hkv}")
+
+
+def test_partial_documents_gaps_and_uncovered_rows():
+    """Only some shards of a document are present; one document has no task; packed KV has rows outside every
+    document and packed Q has rows outside every task: their gradients must come out zero."""
+    b = W.custom([600, 50, 333], [(0, 100, 40), (0, 500, 80), (2, 300, 33)], 4, 2, 128, seed=22)
+    # widen the packed buffers by hand: 7 unused KV rows at the end, 5 unused Q rows at the end
+    b.total_kv += 7
+    b.total_q += 5
+    covered = np.concatenate([np.arange(a, a + n) for a, n in zip(b.task_q_start, b.task_q_len)])
+    hip, ref, _ = full_check(b, "partial", rows=covered)  # rows outside every task have no defined output
+    dk, dv, dq = P.to64(hip["dk"]), P.to64(hip["dv"]), P.to64(hip["dq"])
+    assert np.all(dk[600:650] == 0) and np.all(dv[600:650] == 0)      # document without a task
+    assert np.all(dk[-7:] == 0) and np.all(dv[-7:] == 0)              # outside every document
+    assert np.all(dk[580:600] == 0) and np.all(dv[580:600] == 0)      # beyond the last query (position 579) of document 0
+    assert np.all(dq[-5:] == 0)                                       # outside every task
+    assert np.abs(dv[579]).max() > 0
+
+
+def test_explicit_scale_and_long_kv_len():
+    b = W.custom([400], [(0, 0, 150), (0, 150, 250)], 4, 2, 64, seed=23, scale=0.05)
+    b.task_kv_len[0] = 400  # a prefix longer than needed changes nothing: the mask is causal
+    full_check(b, "scale")
+
+
+def test_duplicate_positions():
+    b = W.custom([300], [(0, 10, 200), (0, 100, 200)], 2, 1, 128, seed=24)
+    full_check(b, "duplicate positions")
+
+
+def test_empty_batch_zeroes_key_gradients():
+    b = W.custom([40], [], 4, 2, 64)
+    q, k, v, d_o = W.make_tensors(b, DEV)
+    hip = P.run_hip(b, q, k, v, d_o)
+    assert torch.all(hip["dk"] == 0) and torch.all(hip["dv"] == 0)
+
+
+def test_composability_is_bit_exact_on_the_gpu():
+    """A document computed as shuffled ragged shards equals the document computed whole, bit for bit: the
+    planner lays both out as the same position-sorted tiles (Section 4.1: the shards' results together
+    are the document's result)."""
+    L = 1500
+    cuts = [0, 16, 48, 49, 300, 811, 1200, L]
+    tasks = [(0, cuts[i], cuts[i + 1] - cuts[i]) for i in range(len(cuts) - 1)] + [(1, 0, 260)]
+    order = [3, 7, 0, 5, 2, 6, 1, 4]
+    sh = W.custom([L, 260], tasks, 8, 2, 128, doc_order=[1, 0], task_order=order, seed=25)
+    wh = W.custom([L, 260], [(0, 0, L), (1, 0, 260)], 8, 2, 128, doc_order=[1, 0], seed=25)
+    qw, k, v, dow = W.make_tensors(wh, DEV)
+    # packed rows of the sharded batch: gather from the whole batch's rows
+    src = np.zeros(sh.total_q, np.int64)
+    for t in range(sh.n_tasks):
+        n = int(sh.task_q_len[t])
+        base = wh.task_q_start[sh.task_doc[t]] + sh.task_q_pos[t]
+        src[sh.task_q_start[t]:sh.task_q_start[t] + n] = base + np.arange(n)
+    idx = torch.as_tensor(src, device=DEV)
+    qs, dos = qw[idx].contiguous(), dow[idx].contiguous()
+    a = P.run_hip(sh, qs, k, v, dos)
+    w = P.run_hip(wh, qw, k, v, dow)
+    assert torch.equal(a["o"], w["o"][idx]) and torch.equal(a["lse"], w["lse"][:, idx])
+    assert torch.equal(a["dq"], w["dq"][idx])
+    assert torch.equal(a["dk"], w["dk"]) and torch.equal(a["dv"], w["dv"])
+    ref = P.run_oracle(wh, qw, k, v, dow)
+    P.assert_parity(P.errors(w, ref), "whole")
+
+
+def test_backward_is_deterministic():
+    b = W.one_kv_group(W.config(3, 16))
+    q, k, v, d_o = W.make_tensors(b, DEV)
+    a = P.run_hip(b, q, k, v, d_o)
+    c = P.run_hip(b, q, k, v, d_o)
+    for n in ("o", "lse", "dq", "dk", "dv"):
+        assert torch.equal(a[n], c[n]), n
+
+
+@pytest.mark.parametrize("idx,n_random", [(2, 192), (3, 256)])
+def test_full_size_workloads_on_exact_subproblems(idx, n_random):
+    """The full workload in the launch configuration the benchmark times; checked where the oracle can compute
+    exact values: sampled query rows (O, LSE, dQ), whole short documents and the last keys of the longest
+    document (dK, dV), for one seeded KV head."""
+    b = W.config(idx)
+    tensors = W.make_tensors(b, DEV)
+    hip = P.run_hip(b, *tensors)
+    for n in ("o", "dq", "dk", "dv"):
+        assert torch.isfinite(hip[n].float()).all(), n
+    kv_head = int(np.random.default_rng(100 + idx).integers(0, b.n_kv_heads))
+    rows = P.sample_rows(b, n_random, seed=idx)
+    e = P.check_sampled_rows(b, tensors, hip, rows, kv_head)
+    e.update(P.check_key_gradients(b, tensors, hip, kv_head))
+    print(f"cfg{idx} full size, kv head {kv_head}:", e, flush=True)
+    assert e["o_err_over_bound"] <= 1.0 and e["lse_max_abs"] <= P.LSE_MAX_ABS and e["dq_rel_l2"] <= P.GRAD_REL_L2
+    assert e["o_max_abs"] <= P.O_MAX_ABS or e["o_elems_ge_4"] > 0
+    for key, val in e.items():
+        if key.endswith("rel_l2"):
+            assert val <= P.GRAD_REL_L2, (key, val)
+    assert e["rows"] >= 256 and e.get("tail_keys", 0) > 0
+
+
+def test_workspace_and_argument_errors():
+    b = W.config(1)
+    q, k, v, d_o = W.make_tensors(b, DEV)
+    plan = B.ca_plan(b)
+    o = torch.empty_like(q)
+    lse = torch.empty((b.n_q_heads, b.total_q), dtype=torch.float32, device=DEV)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    _, need = plan.workspace_bytes()
+    small = torch.empty(need - 256, dtype=torch.uint8, device=DEV)
+    B.ca_forward(plan, q, k, v, o, lse, None)  # forward needs no workspace
+    with pytest.raises(B.CaError) as e:
+        B.ca_backward(plan, q, k, v, o, d_o, lse, dq, dk, dv, small)
+    assert e.value.code == B.CA_ERR_WORKSPACE
+    big = torch.empty(need + 512, dtype=torch.uint8, device=DEV)
+    with pytest.raises(B.CaError) as e:
+        B.ca_backward(plan, q, k, v, o, d_o, lse, dq, dk, dv, big[16:])
+    assert e.value.code == B.CA_ERR_WORKSPACE and "aligned" in e.value.detail
+    lib = B.lib()
+    rc = lib.ca_forward(plan.handle, None, k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(), None, 0, None)
+    assert rc == B.CA_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+
+
+def test_profile_hook_reports_kernel_times():
+    b = W.one_kv_group(W.config(2, 16))
+    q, k, v, d_o = W.make_tensors(b, DEV)
+    plan = B.ca_plan(b)
+    plan.profile_enable(True)
+    hip = P.run_hip(b, q, k, v, d_o, plan=plan)
+    t = plan.profile_read()
+    assert t["fwd_kernel_ms"] > 0 and t["bwd_dkv_ms"] > 0 and t["bwd_dq_ms"] > 0
+    plan.profile_enable(False)

@@ -1,0 +1,186 @@
+"""Host-side planner: descriptor validation (every error path) and schedule invariants.  No GPU needed."""
+import copy
+
+import numpy as np
+import pytest
+
+from paper_2510_18121_amd import binding as B
+from paper_2510_18121_amd import workloads as W
+
+
+def base():
+    return W.custom([40, 300, 17], [(0, 0, 11), (0, 11, 29), (1, 5, 100), (1, 200, 100), (2, 0, 17)], 8, 2, 128,
+                    doc_order=[1, 2, 0], task_order=[3, 0, 4, 2, 1])
+
+
+def plan_error(b):
+    with pytest.raises(B.CaError) as e:
+        B.ca_plan_host(b)
+    return e.value
+
+
+def mutated(**kw):
+    b = copy.deepcopy(base())
+    for k, v in kw.items():
+        if callable(v):
+            v(getattr(b, k))
+        else:
+            setattr(b, k, v)
+    return b
+
+
+def test_valid_descriptor_plans():
+    p = B.ca_plan_host(base())
+    assert p.info()["n_fwd_units"] > 0
+    f, bw = p.workspace_bytes()
+    assert f == 0 and bw > 0 and bw % 256 == 0
+
+
+@pytest.mark.parametrize("name,mut,code,needle", [
+    ("head_dim", dict(head_dim=96), B.CA_ERR_UNSUPPORTED, "head_dim"),
+    ("head ratio", dict(n_q_heads=7), B.CA_ERR_UNSUPPORTED, "multiple"),
+    ("zero heads", dict(n_kv_heads=0), B.CA_ERR_INVALID_ARG, "head counts"),
+    ("q_len 0", dict(task_q_len=lambda a: a.__setitem__(1, 0)), B.CA_ERR_INVALID_ARG, "q_len"),
+    ("bad doc", dict(task_doc=lambda a: a.__setitem__(0, 9)), B.CA_ERR_INVALID_ARG, "names document"),
+    ("q out of range", dict(task_q_start=lambda a: a.__setitem__(1, 10**6)), B.CA_ERR_INVALID_ARG, "outside packed Q"),
+    ("q overlap", dict(task_q_start=lambda a: a.__setitem__(1, int(a[0]) + 1)), B.CA_ERR_INVALID_ARG, "overlap"),
+    ("negative pos", dict(task_q_pos=lambda a: a.__setitem__(0, -1)), B.CA_ERR_INVALID_ARG, "q_pos"),
+    ("row cannot see itself", dict(task_kv_len=lambda a: a.__setitem__(1, 39)), B.CA_ERR_INVALID_ARG, "see itself"),
+    ("kv_len beyond doc", dict(task_kv_len=lambda a: a.__setitem__(1, 41)), B.CA_ERR_INVALID_ARG, "resident KV"),
+    ("doc out of buffer", dict(doc_kv_start=lambda a: a.__setitem__(1, 10**6)), B.CA_ERR_INVALID_ARG, "outside the packed KV"),
+    ("doc overlap", dict(doc_kv_start=lambda a: a.__setitem__(0, int(a[2]))), B.CA_ERR_INVALID_ARG, "overlap"),
+    ("doc len 0", dict(doc_kv_len=lambda a: a.__setitem__(2, 0)), B.CA_ERR_INVALID_ARG, "kv_len"),
+    ("negative totals", dict(total_q=-1), B.CA_ERR_INVALID_ARG, "negative"),
+])
+def test_invalid_descriptors(name, mut, code, needle):
+    err = plan_error(mutated(**mut))
+    assert err.code == code, (name, err)
+    assert needle in err.detail, (name, err.detail)
+
+
+def test_null_arrays_and_null_descriptor():
+    lib = B.lib()
+    keep = []
+    d = B.make_desc(base(), keep)
+    d.task_q_len = None
+    import ctypes
+    h = ctypes.c_void_p()
+    assert lib.ca_plan_host(ctypes.byref(d), ctypes.byref(h)) == B.CA_ERR_INVALID_ARG
+    assert b"null" in lib.ca_last_error()
+    assert lib.ca_plan_host(None, ctypes.byref(h)) == B.CA_ERR_INVALID_ARG
+
+
+def test_using_a_plan_that_was_never_uploaded_is_a_state_error():
+    p = B.ca_plan_host(base())
+    lib = B.lib()
+    rc = lib.ca_forward(p.handle, 1, 1, 1, 1, 1, None, 0, None)
+    assert rc == B.CA_ERR_STATE
+
+
+def check_schedule(b):
+    p = B.ca_plan_host(b)
+    info = p.info()
+    rows, pos = p.rows()
+    bm, bq, bn = info["q_tile_rows"], info["bwd_q_block_rows"], info["kv_tile_rows"]
+    g = b.n_q_heads // b.n_kv_heads
+    assert len(rows) == info["padded_rows"] and len(rows) % bm == 0
+    # every packed query row of every task sits in exactly one slot, with its document position
+    want_pos = np.full(b.total_q, -1, np.int64)
+    want_doc = np.full(b.total_q, -1, np.int64)
+    for t in range(b.n_tasks):
+        sl = slice(int(b.task_q_start[t]), int(b.task_q_start[t] + b.task_q_len[t]))
+        want_pos[sl] = b.task_q_pos[t] + np.arange(b.task_q_len[t])
+        want_doc[sl] = b.task_doc[t]
+    real = rows >= 0
+    assert sorted(rows[real].tolist()) == np.flatnonzero(want_pos >= 0).tolist()
+    assert np.array_equal(pos[real], want_pos[rows[real]])
+    # forward units
+    fu = p.fwd_units()
+    assert len(fu) == info["n_fwd_units"] == info["n_q_tiles"] * b.n_q_heads
+    costs = -(-fu[:, 2] // info["fwd_kv_step"])
+    assert np.all(np.diff(costs) <= 0), "longest first"
+    seen = set()
+    for i, (s0, kv0, nk, h) in enumerate(fu.tolist()):
+        assert s0 % bm == 0 and 0 <= h < b.n_q_heads
+        assert (i % b.n_kv_heads) == h // g, "unit index modulo n_kv_heads is the KV head"
+        tile_rows, tile_pos = rows[s0:s0 + bm], pos[s0:s0 + bm]
+        ok = tile_rows >= 0
+        assert ok.any() and ok[0]
+        docs = set(want_doc[tile_rows[ok]].tolist())
+        assert len(docs) == 1, "rows of different documents never share a tile"
+        dd = docs.pop()
+        assert kv0 == b.doc_kv_start[dd] and nk == tile_pos[ok].max() + 1
+        assert np.all(np.diff(tile_pos) >= 0), "slots sorted by position"
+        assert np.all(tile_pos[~ok] == tile_pos[ok][-1])
+        seen.add((s0, h))
+    assert len(seen) == len(fu)
+    covered = np.zeros(len(rows), bool)
+    for s0 in set(fu[:, 0].tolist()):
+        covered[s0:s0 + bm] = True
+    assert np.all(covered[real])
+    # backward units: every key of every scheduled document once per KV head
+    bu = p.bwd_units()
+    assert len(bu) == info["n_bwd_units"]
+    span = bu[:, 1] - bu[:, 0]
+    assert np.all(np.diff(span) <= 0), "longest first"
+    key_cover = np.zeros((b.total_kv, b.n_kv_heads), np.int32)
+    docs_with_tasks = sorted(set(b.task_doc.tolist()))
+    for i, (sb, se, kvrow, nvalid, kp0, hk) in enumerate(bu.tolist()):
+        assert i % b.n_kv_heads == hk and 1 <= nvalid <= bn and (se - sb) % bq == 0 and se >= sb
+        key_cover[kvrow:kvrow + nvalid, hk] += 1
+        dd = [d for d in docs_with_tasks if b.doc_kv_start[d] <= kvrow < b.doc_kv_start[d] + b.doc_kv_len[d]][0]
+        assert kvrow - b.doc_kv_start[dd] == kp0
+        # slots of this document that can see any key of the tile lie in [sb, se)
+        doc_slots = np.flatnonzero(real & (np.where(real, want_doc[np.maximum(rows, 0)], -1) == dd))
+        sees = doc_slots[pos[doc_slots] >= kp0]
+        if len(sees):
+            assert sb <= sees.min() and sees.max() < se
+        else:
+            assert sb == se
+        if se > sb:
+            assert set(want_doc[rows[sb:se][rows[sb:se] >= 0]].tolist()) == {dd}
+    for dd in docs_with_tasks:
+        sl = slice(int(b.doc_kv_start[dd]), int(b.doc_kv_start[dd] + b.doc_kv_len[dd]))
+        assert np.all(key_cover[sl] == 1)
+    assert key_cover.sum() == sum(int(b.doc_kv_len[d]) for d in docs_with_tasks) * b.n_kv_heads
+    return p
+
+
+def test_schedule_invariants_small_and_ragged():
+    check_schedule(base())
+    check_schedule(W.config(1))
+    # single-row tasks, a document with no task, gaps in positions
+    b = W.custom([5, 9, 700], [(0, 4, 1), (2, 0, 1), (2, 300, 1), (2, 650, 50)], 4, 4, 64, doc_order=[2, 0, 1])
+    check_schedule(b)
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4, 5])
+def test_schedule_invariants_downscaled_workloads(idx):
+    check_schedule(W.config(idx, 16))
+
+
+def test_full_size_plans_build_quickly_and_have_enough_units():
+    import time
+    for idx in (3, 5):
+        b = W.config(idx)
+        t0 = time.perf_counter()
+        p = B.ca_plan_host(b)
+        dt = time.perf_counter() - t0
+        info = p.info()
+        assert dt < 2.0, dt
+        assert info["n_fwd_units"] >= 4 * 256 and info["n_bwd_units"] >= 4 * 256
+        assert info["padded_rows"] - b.total_q <= b.n_docs * info["q_tile_rows"]
+
+
+def test_empty_batch():
+    b = W.custom([8], [], 4, 2, 64)
+    p = B.ca_plan_host(b)
+    assert p.info()["n_fwd_units"] == 0 and p.info()["n_bwd_units"] == 0
+
+
+def test_duplicate_positions_are_allowed_and_sorted():
+    # two tasks of one document covering the same positions (separate query rows)
+    b = W.custom([64], [(0, 10, 20), (0, 15, 20)], 2, 1, 64)
+    p = check_schedule(b)
+    rows, pos = p.rows()
+    assert np.all(np.diff(pos[:40]) >= 0)
