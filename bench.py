@@ -23,16 +23,17 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 
 def cpu_baseline(index: int):
     """The fp64 oracle, as it stands, timed on this host's cores on a bounded sample of the workload:
-    the generator's token-count/16 twin restricted to one KV head's query-head group."""
+    the generator's token-count/8 twin (token-count/32 for the 512K workload) restricted to one KV head's
+    query-head group; about ten seconds of work on 16 cores."""
     import numpy as np
     import oracle
     from paper_2510_18121_amd import workloads as W
 
-    b = W.config(index, 1 if index == 1 else 16)
+    b = W.config(index, 1 if index == 1 else 8)
     if index != 1:
         b = W.one_kv_group(b)
     if index == 4:
-        b = W.one_kv_group(W.config(4, 64))
+        b = W.one_kv_group(W.config(4, 32))
     q, k, v, d_o = W.make_tensors(b, "cpu")
     f64 = lambda t: t.float().numpy().astype(np.float64)
     q, k, v, d_o = f64(q), f64(k), f64(v), f64(d_o)
@@ -51,6 +52,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", type=int, default=3, help="1..5; 3 is the 8B-class 128K-token workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="after the timed steps, run one plain device copy of this many MiB (a kernel of known "
+                         "traffic next to which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported "
@@ -104,6 +108,12 @@ def main():
             kern[kk].append(r[kk])
     kavg = {kk: sum(vv) / len(vv) for kk, vv in kern.items()}
     plan.profile_enable(False)
+    if args.calibration_copy_mib > 0:
+        src = torch.empty(args.calibration_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(3)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
 
     tflops = fl["total"] / (ms_per_step * 1e-3) / 1e12
     # the dK/dV kernel executes 4 of the backward's contractions (S, dP, dV, dK): 8*D*Hq*pairs flops

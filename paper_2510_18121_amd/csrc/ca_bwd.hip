@@ -258,7 +258,10 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
 #pragma unroll
   for (int n = 0; n < NLD; ++n) ld_coff[n] = 8 * ((lane % CH) ^ tile_sw<D>(RPW * wave + RPI * n + ld_rr));
   auto issue_block = [&](int it) {
-    const int blk = it / G, h = hk * G + it % G;
+    // Query blocks are walked from the document's LAST block backwards: every KV tile of a document then
+    // starts at the same block, so the workgroups that run side by side on an XCD (same KV head, neighbouring
+    // KV tiles) fetch the same Q/dO rows at about the same time and share them in that XCD's L2.
+    const int blk = n_blocks - 1 - it / G, h = hk * G + it % G;
     const int s0 = u.slot_begin + blk * BWD_BQ;
     char *st = smem + (it % NST) * S::STAGE;
     // wave-uniform address in the constant address space: scalar loads, which do not enter the
