@@ -1,7 +1,7 @@
 // Backward kernels: dQ, dK, dV of L = sum(dO * O) with P recomputed from the saved log-sum-exp
 // (Section 2.1: P is not stored in forward, it is recomputed during backward).
 //
-//   prep : per (slot, head): Delta = <dO, O> and L2 = log2(e) * LSE, stored in SLOT order (the order of the
+//   prep : per (slot, head): -Delta = -<dO, O> and L2 = log2(e) * LSE, stored in SLOT order (the order of the
 //          planner's per-document sorted query rows), so that both main kernels read them contiguously.
 //          Padding slots get L2 = +huge, which makes their recomputed probabilities exactly 0.
 //   dq   : one workgroup = 256 query slots x one query head (the forward's work units), walking over the
@@ -48,7 +48,7 @@ __global__ void ca_bwd_prep_kernel(const int32_t *__restrict__ slot_row, const b
   }
   for (int o = lanes / 2; o > 0; o >>= 1) s += __shfl_xor(s, o);
   if (ok && c == 0) {
-    delta_slot[int64_t(h) * padded + slot] = row >= 0 ? s : 0.f;
+    delta_slot[int64_t(h) * padded + slot] = row >= 0 ? -s : 0.f;  // stored negated: both kernels add it
     l2_slot[int64_t(h) * padded + slot] = row >= 0 ? LSE[int64_t(h) * total_q + row] * LOG2E : L2_PADDING;
   }
 }
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(512, 2) void ca_bwd_dq_kernel(const FwdUnit *__rest
           if (key > pos) p0 = 0.f;
           if (key + 1 > pos) p1 = 0.f;
         }
-        dw[i >> 1] = pack_bf16(p0 * (pa[i] - dl), p1 * (pa[i + 1] - dl));
+        dw[i >> 1] = pack_bf16(p0 * (pa[i] + dl), p1 * (pa[i + 1] + dl));  // dl holds -Delta
       }
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
@@ -257,41 +257,71 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   int ld_coff[NLD];             // element offset of the lane's chunk in its global row
 #pragma unroll
   for (int n = 0; n < NLD; ++n) ld_coff[n] = 8 * ((lane % CH) ^ tile_sw<D>(RPW * wave + RPI * n + ld_rr));
-  auto issue_block = [&](int it) {
-    // Query blocks are walked from the document's LAST block backwards: every KV tile of a document then
-    // starts at the same block, so the workgroups that run side by side on an XCD (same KV head, neighbouring
-    // KV tiles) fetch the same Q/dO rows at about the same time and share them in that XCD's L2.
-    const int blk = n_blocks - 1 - it / G, h = hk * G + it % G;
-    const int s0 = u.slot_begin + blk * BWD_BQ;
-    char *st = smem + (it % NST) * S::STAGE;
-    // wave-uniform address in the constant address space: scalar loads, which do not enter the
-    // vector-memory counter that paces the direct loads
-    const int32_t CA_CONST *rows = (const int32_t CA_CONST *)(slot_row + s0 + RPW * wave);
-    int rowv[RPW];
+  // Prefetch cursor: (pblk, ph) is the next (query block, head of the group) to fetch.  Query blocks are walked
+  // from the document's LAST block backwards: every KV tile of a document then starts at the same block, so the
+  // workgroups that run side by side on an XCD (same KV head, neighbouring KV tiles) fetch the same Q/dO rows
+  // at about the same time and share them in that XCD's L2.
+  // The G heads of a block use the same rows, so the per-lane row offsets are computed once per block, from
+  // row indices that were fetched with scalar loads (they do not enter the vector-memory counter that paces
+  // the direct loads) while the previous block was being issued.
+  int pblk = n_blocks - 1, ph = 0, pst = 0;
+  int rown[RPW];
+  uint64_t rowoff[NLD];
+  const uint32_t row_bytes = uint32_t(Hq) * D * 2;
+  auto load_rows = [&](int blk) {
+    const int32_t CA_CONST *rows = (const int32_t CA_CONST *)(slot_row + u.slot_begin + blk * BWD_BQ + RPW * wave);
 #pragma unroll
     for (int x = 0; x < RPW; ++x) {
-      rowv[x] = rows[x];
-      asm volatile("" : "+s"(rowv[x]));  // keep it a scalar: no per-lane gather in place of the selects below
+      rown[x] = rows[x];
+      asm volatile("" : "+s"(rown[x]));  // keep it a scalar: no per-lane gather in place of the selects below
     }
+  };
+  int ld_sel[RPI];  // all-ones in the lanes whose row inside a direct load is x
+#pragma unroll
+  for (int x = 0; x < RPI; ++x) ld_sel[x] = ld_rr == x ? -1 : 0;
+  auto make_rowoff = [&]() {
 #pragma unroll
     for (int n = 0; n < NLD; ++n) {
-      int row = rowv[RPI * n];
+      int row = 0;  // branch-free select of this lane's row index out of the RPI scalars of load n
 #pragma unroll
-      for (int x = 1; x < RPI; ++x) row = ld_rr == x ? rowv[RPI * n + x] : row;
-      const size_t off = (size_t(row < 0 ? 0 : row) * Hq + h) * D + ld_coff[n];  // padding slots: any valid row, P is 0
-      load_lds16(Q + off, st + S::Q_OFF + (RPW * wave + RPI * n) * ROWB);
-      load_lds16(dO + off, st + S::DO_OFF + (RPW * wave + RPI * n) * ROWB);
+      for (int x = 0; x < RPI; ++x) row |= ld_sel[x] & rown[RPI * n + x];
+      // padding slots read any valid row: their probabilities are 0
+      rowoff[n] = uint64_t(uint32_t(max(row, 0))) * row_bytes + uint32_t((hk * G * D + ld_coff[n]) * 2);
     }
+  };
+  auto issue_next = [&]() {
+    char *st = smem + pst * S::STAGE;
+    const uint32_t hoff = uint32_t(ph) * D * 2;
+    const char *qb = reinterpret_cast<const char *>(Q) + hoff, *dob = reinterpret_cast<const char *>(dO) + hoff;
+#pragma unroll
+    for (int n = 0; n < NLD; ++n) {
+      load_lds16(qb + rowoff[n], st + S::Q_OFF + (RPW * wave + RPI * n) * ROWB);
+      load_lds16(dob + rowoff[n], st + S::DO_OFF + (RPW * wave + RPI * n) * ROWB);
+    }
+    const int s0 = u.slot_begin + pblk * BWD_BQ, h = hk * G + ph;
     const float *aux = wave == 0 ? l2_slot + int64_t(h) * padded + s0
                      : wave == 1 ? delta_slot + int64_t(h) * padded + s0
                                  : reinterpret_cast<const float *>(slot_pos) + s0;
     char *ad = st + (wave == 0 ? S::L2_OFF : wave == 1 ? S::DL_OFF : wave == 2 ? S::POS_OFF : S::SPARE_OFF);
     load_lds4(aux + lane, ad);
+    pst = pst + 1 == NST ? 0 : pst + 1;
+    if (++ph == G) {
+      ph = 0;
+      if (--pblk >= 0) {
+        make_rowoff();                      // from the indices fetched G iterations ago
+        if (pblk > 0) load_rows(pblk - 1);  // for the block after this one
+      }
+    }
   };
   constexpr int LPI = 2 * NLD + 1;  // loads per wave per iteration
 
-  if (n_it > 0) issue_block(0);
-  if (n_it > 1) issue_block(1);
+  if (n_it > 0) {
+    load_rows(pblk);
+    make_rowoff();
+    if (pblk > 0) load_rows(pblk - 1);
+    issue_next();
+  }
+  if (n_it > 1) issue_next();
 
   // resident K, V fragments of the wave's 32 keys (B operands of S = Q K^T and dP = dO V^T).  Keys past the
   // document's last key are clamped; their positions exceed every query position, so they are masked.
@@ -331,7 +361,7 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
     // block `it` has landed (this wave's part): only the newest block's loads may be in flight
     if (it + 1 < n_it) wait_vmcnt<LPI>(); else wait_vmcnt<0>();
     barrier_nofence();  // ... and everybody else's; everybody is done with block it-1
-    if (it + 2 < n_it) issue_block(it + 2);
+    if (it + 2 < n_it) issue_next();
     const char *st = smem + (it % NST) * S::STAGE;
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
@@ -339,6 +369,13 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
       const int sub_max_pos = *reinterpret_cast<const int *>(st + S::POS_OFF + (32 * qb + 31) * 4);
       if (sub_max_pos < u.key_pos0 + kw0) continue;
       f32x16 sa, pa;
+      f32x4 l2v[4], ndv[4];  // log2e*LSE and -Delta of this lane's 16 query rows
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int qo = (32 * qb + 8 * i4 + 4 * g) * 4;
+        ndv[i4] = *reinterpret_cast<const f32x4 *>(st + S::DL_OFF + qo);
+        l2v[i4] = *reinterpret_cast<const f32x4 *>(st + S::L2_OFF + qo);
+      }
 #pragma unroll
       for (int i = 0; i < 16; ++i) sa[i] = 0.f, pa[i] = 0.f;
       const char *qt = st + S::Q_OFF + 32 * qb * ROWB, *dot = st + S::DO_OFF + 32 * qb * ROWB;
@@ -348,24 +385,30 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
         pa = mfma32(lds_read8(dot + qoff[s]), vf[s], pa);
       }
       uint32_t pw[8], dw[8];
+      // only sub-blocks that straddle the diagonal for this wave's keys need the mask
+      const int sub_min_pos = *reinterpret_cast<const int *>(st + S::POS_OFF + (32 * qb) * 4);
+      if (sub_min_pos >= u.key_pos0 + kw0 + 31) {
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const int qo = (32 * qb + 8 * i4 + 4 * g) * 4;
-        const f32x4 l2v = *reinterpret_cast<const f32x4 *>(st + S::L2_OFF + qo);
-        const f32x4 dlv = *reinterpret_cast<const f32x4 *>(st + S::DL_OFF + qo);
-        const int4 pv = *reinterpret_cast<const int4 *>(st + S::POS_OFF + qo);
-        const int pos4[4] = {pv.x, pv.y, pv.z, pv.w};
-        float p[4], ds[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = 4 * i4 + e;
-          p[e] = key_pos <= pos4[e] ? fast_exp2(fmaf(sa[i], c, -l2v[e])) : 0.f;
-          ds[e] = p[e] * (pa[i] - dlv[e]);
+        for (int i = 0; i < 16; i += 2) {
+          const float p0 = fast_exp2(fmaf(sa[i], c, -l2v[i >> 2][i & 3]));
+          const float p1 = fast_exp2(fmaf(sa[i + 1], c, -l2v[i >> 2][(i & 3) + 1]));
+          pw[i >> 1] = pack_bf16(p0, p1);
+          dw[i >> 1] = pack_bf16(p0 * (pa[i] + ndv[i >> 2][i & 3]), p1 * (pa[i + 1] + ndv[i >> 2][(i & 3) + 1]));
         }
-        pw[2 * i4] = pack_bf16(p[0], p[1]);
-        pw[2 * i4 + 1] = pack_bf16(p[2], p[3]);
-        dw[2 * i4] = pack_bf16(ds[0], ds[1]);
-        dw[2 * i4 + 1] = pack_bf16(ds[2], ds[3]);
+      } else {
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const int4 pv = *reinterpret_cast<const int4 *>(st + S::POS_OFF + (32 * qb + 8 * i4 + 4 * g) * 4);
+          const int pos4[4] = {pv.x, pv.y, pv.z, pv.w};
+          float p[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            p[e] = key_pos <= pos4[e] ? fast_exp2(fmaf(sa[4 * i4 + e], c, -l2v[i4][e])) : 0.f;
+          pw[2 * i4] = pack_bf16(p[0], p[1]);
+          pw[2 * i4 + 1] = pack_bf16(p[2], p[3]);
+          dw[2 * i4] = pack_bf16(p[0] * (pa[4 * i4] + ndv[i4][0]), p[1] * (pa[4 * i4 + 1] + ndv[i4][1]));
+          dw[2 * i4 + 1] = pack_bf16(p[2] * (pa[4 * i4 + 2] + ndv[i4][2]), p[3] * (pa[4 * i4 + 3] + ndv[i4][3]));
+        }
       }
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
