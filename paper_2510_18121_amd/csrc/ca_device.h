@@ -49,6 +49,13 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
+// max of a value with the one held by lane l ^ 32 (v_permlane32_swap: no LDS round trip)
+__device__ __forceinline__ float xor32_max(float x) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__builtin_bit_cast(float, (uint32_t)r[0]), __builtin_bit_cast(float, (uint32_t)r[1]));
+}
+
 __device__ __forceinline__ int wave_max(int v) {
   for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o));
   return v;
@@ -99,6 +106,18 @@ __device__ __forceinline__ void load_lds16(const void *src, char *lds_base_unifo
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :
                : "v"(src), "s"(base)
+               : "memory", "m0");
+}
+// same, addressed as (wave-uniform 64-bit base in SGPRs) + (per-lane unsigned 32-bit byte offset); the LDS
+// destination is a byte offset from the start of LDS
+__device__ __forceinline__ void load_lds16_sbase(const void *base_uniform, uint32_t lane_off, uint32_t lds_off_uniform) {
+  const uint32_t m0v = __builtin_amdgcn_readfirstlane(lds_off_uniform);
+  const uint64_t b = (uint64_t)(uintptr_t)base_uniform;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+  const uint64_t sb = ((uint64_t)hi << 32) | lo;
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(lane_off), "s"(sb), "s"(m0v)
                : "memory", "m0");
 }
 __device__ __forceinline__ void load_lds4(const void *src, char *lds_base_uniform) {

@@ -2,19 +2,21 @@
 // (core attention, Section 2.1; one fused launch over all CA-tasks, Section 4.1).
 //
 // One workgroup = one forward unit = 256 query slots of one document x one query head; 8 waves of
-// 32 slots, two per SIMD, one workgroup per CU.  The wave computes the TRANSPOSED score block S^T = K Q^T with
-// v_mfma_f32_32x32x16_bf16, so that a lane owns one query row (column l%32 of the MFMA result) and its 16
-// registers per block are 16 different keys: row max and row sum are in-lane work plus one exchange
+// 32 slots, two per SIMD, one workgroup per CU.  The wave computes the TRANSPOSED score block S^T = K Q^T
+// with v_mfma_f32_32x32x16_bf16, so that a lane owns one query row (column l%32 of the MFMA result) and its
+// 16 registers per block are 16 different keys: row max and row sum are in-lane work plus one exchange
 // between lanes l and l+32.  The bf16 probabilities, still in those registers, are exactly the B operand of
 // O^T += V^T P^T (the key index is the contraction index; its order inside a block is the same permutation
 // on both operands).  V^T comes out of the natural-layout V tile in LDS through ds_read_b64_tr_b16.
 //
 // K and V tiles of 64 keys go from global memory straight into swizzled LDS tiles (global_load_lds), four
-// stages each, fetched three tiles ahead.  Per tile a wave does three things: the scores of tile j+1
-// (matrix pipe), the softmax of tile j (vector ALU), and P V of tile j (matrix pipe).  Waves 0-3 run them in
-// that order, waves 4-7 (their SIMD partners) run softmax, P V, scores: at any moment the two waves of a SIMD
-// are in different phases, so the vector work of one hides behind the matrix work of the other.  The softmax
-// runs in base 2 with scale*log2(e) folded into one FMA and rescales the accumulators lazily.
+// stages each, fetched three tiles ahead.  The loop is software-pipelined inside the wave at the granularity
+// of 32-key blocks: a step holds the scores of one block (computed one step earlier) and, in ONE basic block,
+// issues the MFMAs of the next block's scores, the exponentials of this block, the MFMAs of this block's P V
+// and the row maximum of the next block, so that the vector work sits in the instruction stream between
+// independent matrix instructions.  That straight-line form is used for tiles entirely below the diagonal of
+// the wave's rows; diagonal tiles take a general path with masking.  The softmax runs in base 2 with scale*log2(e) folded into one FMA and rescales
+// the accumulators lazily.
 #include <type_traits>
 
 #include "ca_device.h"
@@ -32,7 +34,7 @@ struct FwdSmem {
 };
 
 template <int D>
-__global__ __launch_bounds__(512, 2) void ca_fwd_kernel(const FwdUnit *__restrict__ units,
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void ca_fwd_kernel(const FwdUnit *__restrict__ units,
                                                         const int32_t *__restrict__ slot_row,
                                                         const int32_t *__restrict__ slot_pos,
                                                         const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
@@ -51,8 +53,8 @@ __global__ __launch_bounds__(512, 2) void ca_fwd_kernel(const FwdUnit *__restric
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
   const FwdUnit u = units[blockIdx.x];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, r = lane & 31;
-  const int group = wave >> 2;  // 0: scores first, 1: scores last
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, r = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int li = lane & 15, dh = (lane >> 4) & 1;
   const int hk = u.head / (Hq / Hkv);
   const int slot = u.slot0 + wave * 32 + r;
@@ -60,25 +62,33 @@ __global__ __launch_bounds__(512, 2) void ca_fwd_kernel(const FwdUnit *__restric
   const int pos = slot_pos[slot];
   const int wmax = wave_max(pos), wmin = wave_min(pos);
   const int n_tiles = (u.n_keys + FWD_BN - 1) / FWD_BN;
+  // tiles j < n_fast: tile j and the first 32 keys of tile j+1 are entirely visible to every row of this wave
+  const int n_fast = max(0, (wmin - 31) / FWD_BN);
 
   // ---- direct global -> LDS tile loads.  Load n of this wave covers tile rows RPI*(wave + 8n) .. +RPI-1;
   // lane i fills physical chunk i % CH of row i / CH, so it fetches logical chunk (i % CH) ^ sw(row).
-  const int ld_rr = lane / CH;
-  const int ld_row0 = RPI * wave + ld_rr;  // + 8*RPI*n
-  const int ld_chunk = (lane % CH) ^ tile_sw<D>(ld_row0);
-  const size_t kv_stride = size_t(Hkv) * D;
-  const bf16_t *kg = K + (size_t(u.kv_row0) * Hkv + hk) * D + 8 * ld_chunk;
-  const bf16_t *vg = V + (size_t(u.kv_row0) * Hkv + hk) * D + 8 * ld_chunk;
-  const int last_key = u.n_keys - 1;
-  // Tiles past the end are fetched too (clamped to the last key), so that every iteration issues the same
-  // number of loads and the s_waitcnt bookkeeping stays constant.
-  auto issue_kv = [&](const bf16_t *src, int area, int tile) {
-    char *dst = smem + area + (tile % NST) * S::TILE + 1024 * wave;
+  // The address is (scalar tile base) + (per-lane 32-bit offset): advancing to the next tile costs no
+  // vector instruction.  Tiles past the end are fetched too (as the last tile, rows clamped to the last key),
+  // so that every iteration issues the same number of loads and the s_waitcnt bookkeeping stays constant.
+  const uint32_t kv_row_bytes = uint32_t(Hkv) * D * 2;
+  const int ld_row0 = RPI * wave + lane / CH;  // + 8*RPI*n
+  const uint32_t ld_cbytes = uint32_t((lane % CH) ^ tile_sw<D>(ld_row0)) * 16;
+  const int last_tile = n_tiles - 1, last_key_in_tile = u.n_keys - 1 - last_tile * FWD_BN;
+  uint32_t ld_off[NLD], ld_off_last[NLD];
 #pragma unroll
-    for (int n = 0; n < NLD; ++n) {
-      const int key = min(tile * FWD_BN + ld_row0 + 8 * RPI * n, last_key);  // rows past the last key are masked later
-      load_lds16(src + size_t(key) * kv_stride, dst + 8192 * n);
-    }
+  for (int n = 0; n < NLD; ++n) {
+    ld_off[n] = uint32_t(ld_row0 + 8 * RPI * n) * kv_row_bytes + ld_cbytes;
+    ld_off_last[n] = uint32_t(min(ld_row0 + 8 * RPI * n, last_key_in_tile)) * kv_row_bytes + ld_cbytes;
+  }
+  const char *kg = reinterpret_cast<const char *>(K + (size_t(u.kv_row0) * Hkv + hk) * D);
+  const char *vg = reinterpret_cast<const char *>(V + (size_t(u.kv_row0) * Hkv + hk) * D);
+  const size_t tile_bytes = size_t(FWD_BN) * kv_row_bytes;
+  auto issue_kv = [&](const char *src, int area, int tile) __attribute__((always_inline)) {
+    const bool last = tile >= last_tile;
+    const char *base = src + size_t(last ? last_tile : tile) * tile_bytes;
+    const uint32_t dst = uint32_t(area + (tile % NST) * S::TILE + 1024 * wave);
+#pragma unroll
+    for (int n = 0; n < NLD; ++n) load_lds16_sbase(base, last ? ld_off_last[n] : ld_off[n], dst + 8192 * n);
   };
 
   issue_kv(kg, S::K_OFF, 0);
@@ -87,7 +97,6 @@ __global__ __launch_bounds__(512, 2) void ca_fwd_kernel(const FwdUnit *__restric
   issue_kv(vg, S::V_OFF, 1);
   issue_kv(kg, S::K_OFF, 2);
   issue_kv(vg, S::V_OFF, 2);
-  issue_kv(kg, S::K_OFF, 3);
 
   // Q fragments: B operand of S^T = K Q^T; lane holds Q[row][16 s + 8 g .. +7]
   bf16x8 qf[NS];
@@ -97,16 +106,17 @@ __global__ __launch_bounds__(512, 2) void ca_fwd_kernel(const FwdUnit *__restric
     for (int s = 0; s < NS; ++s) qf[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
   }
 
-  // per-lane LDS read offsets inside a tile
-  int koff[NS];  // K fragment s of key row r (second key block: + 32 rows)
+  // per-lane LDS read offsets (bytes from the start of LDS; stage and block offsets are immediates)
+  uint32_t koff[NS];  // K fragment s of key row r (second key block: + 32 rows)
 #pragma unroll
-  for (int s = 0; s < NS; ++s) koff[s] = tile_off<D>(r, 2 * s + g);
-  int voff[2][NDB];  // transposing reads of V: rows 4g + li/4 (+8), 16 head-dim columns of block b
+  for (int s = 0; s < NS; ++s) koff[s] = uint32_t(S::K_OFF + tile_off<D>(r, 2 * s + g));
+  uint32_t voff[2][NDB];  // transposing reads of V: rows 4g + li/4 (+8), 16 head-dim columns of block b
 #pragma unroll
   for (int h2 = 0; h2 < 2; ++h2)
 #pragma unroll
     for (int b = 0; b < NDB; ++b)
-      voff[h2][b] = tile_off<D>(4 * g + (li >> 2) + 8 * h2, 4 * b + 2 * dh + ((li >> 1) & 1)) + 8 * (li & 1);
+      voff[h2][b] = uint32_t(S::V_OFF + tile_off<D>(4 * g + (li >> 2) + 8 * h2, 4 * b + 2 * dh + ((li >> 1) & 1)) +
+                             8 * (li & 1));
 
   f32x16 acc[NDB];
 #pragma unroll
@@ -115,49 +125,26 @@ __global__ __launch_bounds__(512, 2) void ca_fwd_kernel(const FwdUnit *__restric
     for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
   float m = -INFINITY, lsum = 0.f;
 
-  // scores of one tile: two 32-key blocks
-  auto scores = [&](const char *kt, f32x16 &s0, f32x16 &s1) {
+  // scores of one 32-key block: kb = byte offset of (stage, block) inside the K area
+  auto scores = [&](uint32_t kb, f32x16 &s) __attribute__((always_inline)) {
     bf16x8 ka[NS];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) s0[i] = 0.f, s1[i] = 0.f;
+    for (int i = 0; i < 16; ++i) s[i] = 0.f;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) ka[s] = lds_read8(kt + koff[s]);
+    for (int x = 0; x < NS; ++x) ka[x] = lds_read8(smem + (koff[x] + kb));
 #pragma unroll
-    for (int s = 0; s < NS; ++s) s0 = mfma32(ka[s], qf[s], s0);
-#pragma unroll
-    for (int s = 0; s < NS; ++s) ka[s] = lds_read8(kt + koff[s] + 32 * ROWB);
-#pragma unroll
-    for (int s = 0; s < NS; ++s) s1 = mfma32(ka[s], qf[s], s1);
+    for (int x = 0; x < NS; ++x) s = mfma32(ka[x], qf[x], s);
   };
-
-  f32x16 n0, n1;  // scores of the next tile
-  // Everything issued so far has landed, including the Q fragments: from here on the compiler places no
-  // vector-memory waits inside the loop (they would drain the direct-load queue every iteration).
-  wait_vmcnt<0>();
+  auto row_max = [&](const f32x16 &s) __attribute__((always_inline)) {
+    float a = fmaxf(s[0], s[1]), b = fmaxf(s[8], s[9]);  // two chains
 #pragma unroll
-  for (int s = 0; s < NS; ++s) pin(qf[s]);
-  barrier_nofence();
-  scores(smem + S::K_OFF, n0, n1);
-
-  auto softmax_pv = [&](int j, f32x16 s0, f32x16 s1) {
-    const int j0 = j * FWD_BN;
-    if (j0 + FWD_BN - 1 > wmin) {  // some (row, key) of this tile is above the diagonal
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key = j0 + (i >> 2) * 8 + 4 * g + (i & 3);
-        if (key > pos) s0[i] = -INFINITY;
-        if (key + 32 > pos) s1[i] = -INFINITY;
-      }
-    }
-    float mx = s0[0];
-#pragma unroll
-    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s0[i]);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s1[i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    // Lazy rescaling: the running reference m only moves when some row's maximum has grown by more than
-    // 2^RESCALE_LOG2; until then probabilities are taken relative to the stale m (they stay below
-    // 2^RESCALE_LOG2, harmless in fp32 and bf16) and the accumulators need no multiply.
+    for (int i = 2; i < 8; ++i) a = fmaxf(a, s[i]), b = fmaxf(b, s[8 + i]);
+    return xor32_max(fmaxf(a, b));
+  };
+  // Lazy rescaling: the running reference m only moves when some row's maximum has grown by more than
+  // 2^RESCALE_LOG2; until then probabilities are taken relative to the stale m (they stay below
+  // 2^RESCALE_LOG2, harmless in fp32 and bf16) and the accumulators need no multiply.
+  auto rescale = [&](float mx) __attribute__((always_inline)) {
     const float m_cand = fmaxf(m, mx * c);
     if (__any(m_cand > m + RESCALE_LOG2)) {
       const float alpha = m == -INFINITY ? 0.f : fast_exp2(m - m_cand);
@@ -168,83 +155,151 @@ __global__ __launch_bounds__(512, 2) void ca_fwd_kernel(const FwdUnit *__restric
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[b][i] *= alpha;
     }
-    float psum = 0.f;
+  };
+  // exponentials of a block's scores (in place), row-sum update, packing into the two B operands of P V:
+  // k-step t uses registers 8t .. 8t+7
+  auto exp_pack = [&](f32x16 &s, bf16x8 (&pb)[2]) {
+    float p0 = 0.f, p1 = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      s0[i] = fast_exp2(fmaf(s0[i], c, -m));
-      s1[i] = fast_exp2(fmaf(s1[i], c, -m));
-      psum += s0[i] + s1[i];
+    for (int i = 0; i < 8; ++i) {
+      s[i] = fast_exp2(fmaf(s[i], c, -m));
+      s[8 + i] = fast_exp2(fmaf(s[8 + i], c, -m));
+      p0 += s[i];
+      p1 += s[8 + i];
     }
-    lsum += psum;
-    // P^T as B operands: k-step t of key block kb uses registers 8t .. 8t+7
-    bf16x8 pb[4];
+    lsum += p0 + p1;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-      u32x4 w0 = {pack_bf16(s0[8 * t], s0[8 * t + 1]), pack_bf16(s0[8 * t + 2], s0[8 * t + 3]),
-                  pack_bf16(s0[8 * t + 4], s0[8 * t + 5]), pack_bf16(s0[8 * t + 6], s0[8 * t + 7])};
-      u32x4 w1 = {pack_bf16(s1[8 * t], s1[8 * t + 1]), pack_bf16(s1[8 * t + 2], s1[8 * t + 3]),
-                  pack_bf16(s1[8 * t + 4], s1[8 * t + 5]), pack_bf16(s1[8 * t + 6], s1[8 * t + 7])};
-      pb[t] = __builtin_bit_cast(bf16x8, w0);
-      pb[2 + t] = __builtin_bit_cast(bf16x8, w1);
+      u32x4 w = {pack_bf16(s[8 * t], s[8 * t + 1]), pack_bf16(s[8 * t + 2], s[8 * t + 3]),
+                 pack_bf16(s[8 * t + 4], s[8 * t + 5]), pack_bf16(s[8 * t + 6], s[8 * t + 7])};
+      pb[t] = __builtin_bit_cast(bf16x8, w);
     }
-    const char *vt = smem + S::V_OFF + (j % NST) * S::TILE;
+  };
+  // vb = byte offset of (stage, block) inside the V area
+  auto pv = [&](uint32_t vb, const bf16x8 (&pb)[2]) {
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt) {  // keys 16 kt .. 16 kt + 15 of the tile
+    for (int t = 0; t < 2; ++t) {  // keys 16 t .. 16 t + 15 of the block
 #pragma unroll
       for (int b = 0; b < NDB; ++b) {
-        bf16x8 a = join(lds_read_tr4(vt + voff[0][b] + 16 * kt * ROWB), lds_read_tr4(vt + voff[1][b] + 16 * kt * ROWB));
-        acc[b] = mfma32(a, pb[kt], acc[b]);
+        bf16x8 a = join(lds_read_tr4(smem + (voff[0][b] + vb + 16 * t * ROWB)),
+                        lds_read_tr4(smem + (voff[1][b] + vb + 16 * t * ROWB)));
+        acc[b] = mfma32(a, pb[t], acc[b]);
       }
     }
+  };
+
+  // Everything issued so far has landed, including the Q fragments: from here on the compiler places no
+  // vector-memory waits inside the loop (they would drain the direct-load queue every iteration).
+  wait_vmcnt<0>();
+#pragma unroll
+  for (int s = 0; s < NS; ++s) pin(qf[s]);
+  barrier_nofence();
+
+  // The pipeline unit is a 32-key block.  cur holds the scores of the block about to be exponentiated
+  // (block 0 of tile j at the top of iteration j), nxt receives the following block's.
+  f32x16 cur, nxt;
+  scores(0, cur);
+  float mx_cur = row_max(cur), mx_nxt = 0.f;
+
+  auto top = [&](int j) __attribute__((always_inline)) {
+    // this wave's parts of K(j+1) and V(j) have landed: only the loads of tiles j+2 of K and j+1, j+2 of V
+    // may still be in flight
+    wait_vmcnt<3 * NLD>();
+    barrier_nofence();  // ... and everybody else's; everybody is done with K(j-1) and V(j-1)
+    issue_kv(kg, S::K_OFF, j + 3);
+    issue_kv(vg, S::V_OFF, j + 3);
+  };
+
+  // Instruction order of one pipeline step (a hint to the scheduler; the hardware issues a wave's instructions
+  // in order, so vector work only overlaps matrix work that surrounds it in the stream): the 8 K-fragment reads,
+  // then every score MFMA followed by a share of the exponentials, then every P V MFMA preceded by its two
+  // transposing reads and followed by a share of the row maximum.
+  auto interleave = [&]() __attribute__((always_inline)) {
+    __builtin_amdgcn_sched_group_barrier(0x100, NS, 0);  // DS reads
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);  // VALU
+    }
+#pragma unroll
+    for (int i = 0; i < 2 * NDB; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+    }
+  };
+
+  // Tile j and block 0 of tile j+1 fully visible: no mask, no skip.  After each (rare) rescale there is one
+  // basic block with 8 score MFMAs, 16 exponentials, 8 P V MFMAs and a row maximum, all mutually independent
+  // except through the bf16 P operands.
+  auto fast = [&](int j, auto st_c) __attribute__((always_inline)) {
+    const int ST = st_c;
+    top(j);
+    bf16x8 pb[2];
+    rescale(mx_cur);
+    scores(uint32_t(ST * S::TILE + 32 * ROWB), nxt);
+    exp_pack(cur, pb);
+    pv(uint32_t(ST * S::TILE), pb);
+    mx_nxt = row_max(nxt);
+    rescale(mx_nxt);
+    scores(uint32_t(((ST + 1) % NST) * S::TILE), cur);
+    exp_pack(nxt, pb);
+    pv(uint32_t(ST * S::TILE + 32 * ROWB), pb);
+    mx_cur = row_max(cur);
+  };
+
+  // general path: diagonal tiles (mask), tiles some waves do not see at all, the first tile of a document
+  auto tail_block = [&](int j, int kb, f32x16 &x) __attribute__((always_inline)) {
+    const int k0 = j * FWD_BN + 32 * kb;
+    if (k0 > wmax) return;
+    if (k0 + 31 > wmin) {  // some (row, key) of this block is above the diagonal
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if (k0 + (i >> 2) * 8 + 4 * g + (i & 3) > pos) x[i] = -INFINITY;
+    }
+    rescale(row_max(x));
+    bf16x8 pb[2];
+    exp_pack(x, pb);
+    const uint32_t vb = uint32_t((j % NST) * S::TILE + 32 * kb * ROWB);
+    pv(vb, pb);
     // The first rows of a document see a handful of keys, their output is as large as a single V row, and
     // the 2^-9 relative rounding of P to bf16 then shows up at the 1e-2 level next to the output's own bf16
     // rounding.  For the waves that hold such rows, the rounding residue of P is fed through the matrix pipe
     // as a second bf16 operand (P = hi + lo), which makes P V as good as fp32 at negligible cost: it
     // happens only in the first tile of the first query rows of each document.
     if (j == 0 && wmin < FWD_BN) {
-      bf16x8 pl[4];
+      bf16x8 pl[2];
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        uint32_t l0[4], l1[4];
+        uint32_t lo[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const uint32_t h0 = __builtin_bit_cast(u32x4, pb[t])[e], h1 = __builtin_bit_cast(u32x4, pb[2 + t])[e];
-          l0[e] = pack_bf16(s0[8 * t + 2 * e] - __uint_as_float(h0 << 16),
-                            s0[8 * t + 2 * e + 1] - __uint_as_float(h0 & 0xffff0000u));
-          l1[e] = pack_bf16(s1[8 * t + 2 * e] - __uint_as_float(h1 << 16),
-                            s1[8 * t + 2 * e + 1] - __uint_as_float(h1 & 0xffff0000u));
+          const uint32_t h = __builtin_bit_cast(u32x4, pb[t])[e];
+          lo[e] = pack_bf16(x[8 * t + 2 * e] - __uint_as_float(h << 16),
+                            x[8 * t + 2 * e + 1] - __uint_as_float(h & 0xffff0000u));
         }
-        pl[t] = __builtin_bit_cast(bf16x8, u32x4{l0[0], l0[1], l0[2], l0[3]});
-        pl[2 + t] = __builtin_bit_cast(bf16x8, u32x4{l1[0], l1[1], l1[2], l1[3]});
+        pl[t] = __builtin_bit_cast(bf16x8, u32x4{lo[0], lo[1], lo[2], lo[3]});
       }
-#pragma unroll
-      for (int kt = 0; kt < 4; ++kt) {
-#pragma unroll
-        for (int b = 0; b < NDB; ++b) {
-          bf16x8 a = join(lds_read_tr4(vt + voff[0][b] + 16 * kt * ROWB), lds_read_tr4(vt + voff[1][b] + 16 * kt * ROWB));
-          acc[b] = mfma32(a, pl[kt], acc[b]);
-        }
-      }
+      pv(vb, pl);
     }
+  };
+  auto tail = [&](int j) __attribute__((always_inline)) {
+    const int j0 = j * FWD_BN;
+    top(j);
+    if (j0 + 32 <= wmax) scores(uint32_t((j % NST) * S::TILE + 32 * ROWB), nxt);
+    tail_block(j, 0, cur);
+    if (j + 1 < n_tiles && j0 + FWD_BN <= wmax) {
+      scores(uint32_t(((j + 1) % NST) * S::TILE), cur);
+      mx_cur = row_max(cur);
+    }
+    tail_block(j, 1, nxt);
   };
 
   for (int j = 0; j < n_tiles; ++j) {
-    const int j0 = j * FWD_BN;
-    const f32x16 s0 = n0, s1 = n1;
-    // this wave's parts of K(j+1) and V(j) have landed: only the loads of the last two iterations
-    // (tiles j+2, j+3 of V and j+3, j+4 of K) may still be in flight
-    wait_vmcnt<4 * NLD>();
-    barrier_nofence();  // ... and everybody else's; everybody is done with K(j) and V(j-1)
-    issue_kv(vg, S::V_OFF, j + 3);
-    issue_kv(kg, S::K_OFF, j + 4);
-    const bool next = j + 1 < n_tiles && j0 + FWD_BN <= wmax;
-    const char *kn = smem + S::K_OFF + ((j + 1) % NST) * S::TILE;
-    if (group == 0) {
-      if (next) scores(kn, n0, n1);
-      if (j0 <= wmax) softmax_pv(j, s0, s1);
+    if (j < n_fast) {
+      fast(j, j & 3);
     } else {
-      if (j0 <= wmax) softmax_pv(j, s0, s1);
-      if (next) scores(kn, n0, n1);
+      tail(j);
     }
   }
   wait_vmcnt<0>();  // nothing may still be writing LDS when the workgroup ends
