@@ -84,7 +84,8 @@ __global__ __launch_bounds__(512, 2) void ca_bwd_dq_kernel(const FwdUnit *__rest
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
   const FwdUnit u = units[blockIdx.x];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, r = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, r = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int li = lane & 15, dh = (lane >> 4) & 1;
   const int hk = u.head / (Hq / Hkv);
   const int slot = u.slot0 + wave * 32 + r;
@@ -96,19 +97,27 @@ __global__ __launch_bounds__(512, 2) void ca_bwd_dq_kernel(const FwdUnit *__rest
   const int n_tiles = (u.n_keys + FWD_BN - 1) / FWD_BN;
   const float c = scale * LOG2E;
 
+  // direct loads addressed as (scalar tile base) + (per-lane 32-bit offset); tiles past the end are fetched as the
+  // last tile with rows clamped to the last key (constant number of loads per iteration, see the forward kernel)
+  const uint32_t kv_row_bytes = uint32_t(Hkv) * D * 2;
   const int ld_row0 = RPI * wave + lane / CH;  // + 8*RPI*n
-  const int ld_chunk = (lane % CH) ^ tile_sw<D>(ld_row0);
-  const size_t kv_stride = size_t(Hkv) * D;
-  const bf16_t *kg = K + (size_t(u.kv_row0) * Hkv + hk) * D + 8 * ld_chunk;
-  const bf16_t *vg = V + (size_t(u.kv_row0) * Hkv + hk) * D + 8 * ld_chunk;
-  const int last_key = u.n_keys - 1;
-  auto issue_kv = [&](const bf16_t *src, int area, int tile) {  // same count every iteration (see forward)
-    char *dst = smem + area + (tile % NST) * S::TILE + 1024 * wave;
+  const uint32_t ld_cbytes = uint32_t((lane % CH) ^ tile_sw<D>(ld_row0)) * 16;
+  const int last_tile = n_tiles - 1, last_key_in_tile = u.n_keys - 1 - last_tile * FWD_BN;
+  uint32_t ld_off[NLD], ld_off_last[NLD];
 #pragma unroll
-    for (int n = 0; n < NLD; ++n) {
-      const int key = min(tile * FWD_BN + ld_row0 + 8 * RPI * n, last_key);
-      load_lds16(src + size_t(key) * kv_stride, dst + 8192 * n);
-    }
+  for (int n = 0; n < NLD; ++n) {
+    ld_off[n] = uint32_t(ld_row0 + 8 * RPI * n) * kv_row_bytes + ld_cbytes;
+    ld_off_last[n] = uint32_t(min(ld_row0 + 8 * RPI * n, last_key_in_tile)) * kv_row_bytes + ld_cbytes;
+  }
+  const char *kg = reinterpret_cast<const char *>(K + (size_t(u.kv_row0) * Hkv + hk) * D);
+  const char *vg = reinterpret_cast<const char *>(V + (size_t(u.kv_row0) * Hkv + hk) * D);
+  const size_t tile_bytes = size_t(FWD_BN) * kv_row_bytes;
+  auto issue_kv = [&](const char *src, int area, int tile) __attribute__((always_inline)) {
+    const bool last = tile >= last_tile;
+    const char *base = src + size_t(last ? last_tile : tile) * tile_bytes;
+    const uint32_t dst = uint32_t(area + (tile % NST) * S::TILE + 1024 * wave);
+#pragma unroll
+    for (int n = 0; n < NLD; ++n) load_lds16_sbase(base, last ? ld_off_last[n] : ld_off[n], dst + 8192 * n);
   };
   issue_kv(kg, S::K_OFF, 0);
   issue_kv(vg, S::V_OFF, 0);
