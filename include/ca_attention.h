@@ -130,8 +130,9 @@ int ca_plan_info(const ca_plan_t *plan, int64_t *out, int n);
  *  rows : [padded_rows] packed Q row of each tile slot, -1 for padding
  *  pos  : [padded_rows] document position of each tile slot
  *  fwd  : [n_fwd_units][4] = {first slot, packed KV row of doc token 0, keys needed (max pos + 1), head}
- *  bwd  : [n_bwd_units][6] = {first slot of first q block, slots end, packed KV row of the tile's first key,
- *                             valid keys in tile, document position of the tile's first key, KV head}
+ *  bwd  : [n_bwd_units][7] = {first slot of first q block, slots end, first slot from which every slot sees the
+ *                             whole tile, packed KV row of the tile's first key, valid keys in tile, document
+ *                             position of the tile's first key, KV head}
  */
 int64_t ca_plan_rows(const ca_plan_t *plan, int32_t *rows, int32_t *pos);
 int64_t ca_plan_fwd_units(const ca_plan_t *plan, int32_t *units);

@@ -247,6 +247,8 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   constexpr int NLD = BWD_BQ / (4 * RPI);  // direct loads per wave per Q (or dO) tile
   constexpr int RPW = BWD_BQ / 4;          // tile rows fetched by one wave (contiguous)
   constexpr int ROWB = 2 * D;
+  constexpr int PA = NS < 4 ? NS : 4;      // k-steps of natural Q/dO fragments held ahead of their MFMAs
+  constexpr int PFB = (2 * PA) / (2 * NDB);  // natural fragments fetched per gradient MFMA pair
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
   const BwdUnit u = units[blockIdx.x];
@@ -259,9 +261,12 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   const int key_pos = u.key_pos0 + kw0 + r;  // document position of this lane's key
   const int n_blocks = (u.slot_end - u.slot_begin) / BWD_BQ;
   const int n_it = n_blocks * G;
+  // Query blocks are walked from the last one backwards (below), so the blocks that lie entirely below the
+  // diagonal of this KV tile come first: they take the pipelined path without mask.
+  const int n_fast = ((u.slot_end - u.slot_full) / BWD_BQ) * G;
 
-  // ---- loads of one (q block, head): this wave fetches tile rows RPW*wave .. +RPW-1 of Q and of dO
-  // (row indices through scalar loads), plus one 64-float auxiliary array.
+  // ---- loads of one (q block, head): this wave fetches tile rows RPW*wave .. +RPW-1 of Q and of dO, plus one
+  // 64-float auxiliary array.
   const int ld_rr = lane / CH;  // row inside one direct load
   int ld_coff[NLD];             // element offset of the lane's chunk in its global row
 #pragma unroll
@@ -272,12 +277,13 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   // at about the same time and share them in that XCD's L2.
   // The G heads of a block use the same rows, so the per-lane row offsets are computed once per block, from
   // row indices that were fetched with scalar loads (they do not enter the vector-memory counter that paces
-  // the direct loads) while the previous block was being issued.
+  // the direct loads) while the previous block was being issued.  Past the last block the cursor stays on it:
+  // every iteration issues the same number of loads, which keeps the s_waitcnt bookkeeping constant.
   int pblk = n_blocks - 1, ph = 0, pst = 0;
   int rown[RPW];
   uint64_t rowoff[NLD];
   const uint32_t row_bytes = uint32_t(Hq) * D * 2;
-  auto load_rows = [&](int blk) {
+  auto load_rows = [&](int blk) __attribute__((always_inline)) {
     const int32_t CA_CONST *rows = (const int32_t CA_CONST *)(slot_row + u.slot_begin + blk * BWD_BQ + RPW * wave);
 #pragma unroll
     for (int x = 0; x < RPW; ++x) {
@@ -288,7 +294,7 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   int ld_sel[RPI];  // all-ones in the lanes whose row inside a direct load is x
 #pragma unroll
   for (int x = 0; x < RPI; ++x) ld_sel[x] = ld_rr == x ? -1 : 0;
-  auto make_rowoff = [&]() {
+  auto make_rowoff = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int n = 0; n < NLD; ++n) {
       int row = 0;  // branch-free select of this lane's row index out of the RPI scalars of load n
@@ -298,7 +304,7 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
       rowoff[n] = uint64_t(uint32_t(max(row, 0))) * row_bytes + uint32_t((hk * G * D + ld_coff[n]) * 2);
     }
   };
-  auto issue_next = [&]() {
+  auto issue_next = [&]() __attribute__((always_inline)) {
     char *st = smem + pst * S::STAGE;
     const uint32_t hoff = uint32_t(ph) * D * 2;
     const char *qb = reinterpret_cast<const char *>(Q) + hoff, *dob = reinterpret_cast<const char *>(dO) + hoff;
@@ -315,10 +321,13 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
     load_lds4(aux + lane, ad);
     pst = pst + 1 == NST ? 0 : pst + 1;
     if (++ph == G) {
-      ph = 0;
-      if (--pblk >= 0) {
+      if (pblk > 0) {
+        ph = 0;
+        --pblk;
         make_rowoff();                      // from the indices fetched G iterations ago
         if (pblk > 0) load_rows(pblk - 1);  // for the block after this one
+      } else {
+        ph = G - 1;  // past the end: keep re-fetching the final (block, head)
       }
     }
   };
@@ -328,9 +337,10 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
     load_rows(pblk);
     make_rowoff();
     if (pblk > 0) load_rows(pblk - 1);
+    issue_next();  // blocks 0, 1, 2: three ahead
+    issue_next();
     issue_next();
   }
-  if (n_it > 1) issue_next();
 
   // resident K, V fragments of the wave's 32 keys (B operands of S = Q K^T and dP = dO V^T).  Keys past the
   // document's last key are clamped; their positions exceed every query position, so they are masked.
@@ -361,79 +371,205 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
     for (int i = 0; i < 16; ++i) acc_dk[b][i] = 0.f, acc_dv[b][i] = 0.f;
 
   // All register loads above are complete from here on, so the compiler places no vector-memory waits
-  // inside the loop (they would drain the direct-load queue every iteration).
+  // inside the loops (they would drain the direct-load queue every iteration).
   wait_vmcnt<0>();
 #pragma unroll
-  for (int s = 0; s < NS; ++s) pin(kf[s]), pin(vf[s]);
+  for (int s = 0; s < NS; ++s) pin_acc(kf[s]), pin_acc(vf[s]);
+  barrier_nofence();
 
-  for (int it = 0; it < n_it; ++it) {
-    // block `it` has landed (this wave's part): only the newest block's loads may be in flight
-    if (it + 1 < n_it) wait_vmcnt<LPI>(); else wait_vmcnt<0>();
-    barrier_nofence();  // ... and everybody else's; everybody is done with block it-1
-    if (it + 2 < n_it) issue_next();
-    const char *st = smem + (it % NST) * S::STAGE;
+  // ------------------------------------------------------------------------------------------------
+  // Pipelined path for blocks entirely below the diagonal.  With one wave per SIMD nothing hides an LDS
+  // latency except this wave's own MFMAs, so every MFMA finds its LDS operand already in registers:
+  //   * score phase (S, dP: 2 NS MFMAs): natural Q/dO fragments, held PA k-steps ahead and re-fetched as they
+  //     are consumed; meanwhile the first half of the transposed fragments of this sub-block is fetched;
+  //   * vector phase: P = exp2(c S - L2), dS = P (dP - Delta), packed to bf16;
+  //   * gradient phase (dV, dK: 4 NDB MFMAs): transposed dO/Q fragments, second half re-fetched into the
+  //     registers of the first as it is consumed; meanwhile the natural fragments of the NEXT sub-block are
+  //     fetched.
+  // sched_barrier fences pin that order.  The barrier for the next block sits in the middle of the last gradient
+  // phase of an iteration: after it no wave reads this iteration's LDS stage any more (the rest of the phase works
+  // from registers), so the stage can be refilled at once, three blocks ahead with three stages.
+  bf16x8 opq[PA], opd[PA];  // natural fragments, k-steps s .. s+PA-1 of the sub-block in flight
+  bf16x8 opb[2 * NDB];      // transposed fragments: [2b] = dO^T, [2b+1] = Q^T of column block b
+  // qoff / toff / auxo are kept as byte offsets into the CURRENT stage and advanced once per iteration, so that
+  // every LDS read is (loop-carried register) + (immediate).
+  int auxo = 16 * g;
+  int stage = 0;
+  auto advance_stage = [&]() __attribute__((always_inline)) {
+    const int adv = stage == NST - 1 ? -(NST - 1) * S::STAGE : S::STAGE;
+    stage = stage == NST - 1 ? 0 : stage + 1;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) qoff[s] += adv;
+#pragma unroll
+    for (int b = 0; b < NDB; ++b) toff[0][b] += adv, toff[1][b] += adv;
+    auxo += adv;
+  };
+  constexpr int SUB = 32 * ROWB, HALF = 16 * ROWB;
+  if (n_fast > 0) {
+#pragma unroll
+    for (int s = 0; s < PA; ++s) {
+      opq[s] = lds_read8(smem + S::Q_OFF + qoff[s]);
+      opd[s] = lds_read8(smem + S::DO_OFF + qoff[s]);
+    }
+  }
+  int it = 0;
+  for (; it < n_fast; ++it) {
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
+      const int QT = S::Q_OFF + qb * SUB, DOT = S::DO_OFF + qb * SUB;  // sub-block tiles inside the stage
+      f32x16 sa, pa;
+      // ---- score phase
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        if (s == 0) {
+          mfma32_v_first(sa, opq[0], kf[0]);
+          mfma32_v_first(pa, opd[0], vf[0]);
+        } else {
+          mfma32_v(sa, opq[s % PA], kf[s]);
+          mfma32_v(pa, opd[s % PA], vf[s]);
+        }
+        if (s + PA < NS) {
+          opq[s % PA] = lds_read8(smem + QT + qoff[s + PA]);
+          opd[s % PA] = lds_read8(smem + DOT + qoff[s + PA]);
+        }
+        {  // transposed fragment s of the first half (rows 0..15 of the sub-block)
+          const int X = (s & 1) ? QT : DOT;
+          opb[s] = join(lds_read_tr4(smem + X + toff[0][s >> 1]), lds_read_tr4(smem + X + toff[1][s >> 1]));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // ---- vector phase (the auxiliary reads travel while the last MFMA drains)
+      f32x4 ndv[4], l2v[4];
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int qo = (32 * qb + 8 * i4) * 4;
+        ndv[i4] = *reinterpret_cast<const f32x4 *>(smem + S::DL_OFF + qo + auxo);
+        l2v[i4] = *reinterpret_cast<const f32x4 *>(smem + S::L2_OFF + qo + auxo);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_settle(sa, pa);
+      uint32_t pw[8], dw[8];
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        float p[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) p[e] = fast_exp2(fmaf(sa[4 * i4 + e], c, -l2v[i4][e]));
+        pw[2 * i4] = pack_bf16(p[0], p[1]);
+        pw[2 * i4 + 1] = pack_bf16(p[2], p[3]);
+        dw[2 * i4] = pack_bf16(p[0] * (pa[4 * i4] + ndv[i4][0]), p[1] * (pa[4 * i4 + 1] + ndv[i4][1]));
+        dw[2 * i4 + 1] = pack_bf16(p[2] * (pa[4 * i4 + 2] + ndv[i4][2]), p[3] * (pa[4 * i4 + 3] + ndv[i4][3]));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      // ---- gradient phase
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        if (qb == 1 && t == 1) {
+          // All LDS reads of this iteration's stage have been issued (the transposed second half just above);
+          // block it+1 has landed (this wave's part): only block it+2 may be in flight.
+          wait_vmcnt<LPI>();
+          barrier_nofence();  // waits for this wave's LDS reads, then for everybody
+          issue_next();       // block it+3 into the stage of block it
+          advance_stage();    // the offsets now address block it+1
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        const bf16x8 pb = __builtin_bit_cast(bf16x8, u32x4{pw[4 * t], pw[4 * t + 1], pw[4 * t + 2], pw[4 * t + 3]});
+        const bf16x8 db = __builtin_bit_cast(bf16x8, u32x4{dw[4 * t], dw[4 * t + 1], dw[4 * t + 2], dw[4 * t + 3]});
+#pragma unroll
+        for (int b = 0; b < NDB; ++b) {
+          acc_dv[b] = mfma32(opb[2 * b], pb, acc_dv[b]);
+          acc_dk[b] = mfma32(opb[2 * b + 1], db, acc_dk[b]);
+          if (t == 0) {  // second half of this sub-block (rows 16..31) into the registers just consumed
+            opb[2 * b] = join(lds_read_tr4(smem + DOT + HALF + toff[0][b]), lds_read_tr4(smem + DOT + HALF + toff[1][b]));
+            opb[2 * b + 1] = join(lds_read_tr4(smem + QT + HALF + toff[0][b]), lds_read_tr4(smem + QT + HALF + toff[1][b]));
+          }
+          // natural fragments of the next sub-block: second half of this stage for qb == 0 (spread over both
+          // halves of the phase), first half of the next stage for qb == 1 (only after the barrier)
+          if (qb == 0) {
+#pragma unroll
+            for (int x = 0; x < PFB; ++x) {
+              const int o = (t * NDB + b) * PFB + x, sn = o >> 1;
+              if (o & 1) opd[sn] = lds_read8(smem + S::DO_OFF + SUB + qoff[sn]);
+              else opq[sn] = lds_read8(smem + S::Q_OFF + SUB + qoff[sn]);
+            }
+          } else if (t == 1) {
+#pragma unroll
+            for (int x = 0; x < 2 * PFB; ++x) {
+              const int o = b * 2 * PFB + x, sn = o >> 1;
+              if (o & 1) opd[sn] = lds_read8(smem + S::DO_OFF + qoff[sn]);
+              else opq[sn] = lds_read8(smem + S::Q_OFF + qoff[sn]);
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+  }
+
+  // ------------------------------------------------------------------------------------------------
+  // General path: blocks that straddle the diagonal (mask, skip of invisible sub-blocks).  One barrier before
+  // and one after the compute, then the refill of this stage.
+  for (; it < n_it; ++it) {
+    wait_vmcnt<2 * LPI>();  // block `it` has landed (this wave's part); blocks it+1, it+2 may be in flight
+    barrier_nofence();
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const int QT = S::Q_OFF + qb * SUB, DOT = S::DO_OFF + qb * SUB;
       // sub-block entirely above the diagonal for this wave's keys? (slot positions are sorted)
-      const int sub_max_pos = *reinterpret_cast<const int *>(st + S::POS_OFF + (32 * qb + 31) * 4);
+      const int sub_max_pos = *reinterpret_cast<const int *>(smem + stage * S::STAGE + S::POS_OFF + (32 * qb + 31) * 4);
       if (sub_max_pos < u.key_pos0 + kw0) continue;
       f32x16 sa, pa;
       f32x4 l2v[4], ndv[4];  // log2e*LSE and -Delta of this lane's 16 query rows
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        const int qo = (32 * qb + 8 * i4 + 4 * g) * 4;
-        ndv[i4] = *reinterpret_cast<const f32x4 *>(st + S::DL_OFF + qo);
-        l2v[i4] = *reinterpret_cast<const f32x4 *>(st + S::L2_OFF + qo);
+        const int qo = (32 * qb + 8 * i4) * 4;
+        ndv[i4] = *reinterpret_cast<const f32x4 *>(smem + S::DL_OFF + qo + auxo);
+        l2v[i4] = *reinterpret_cast<const f32x4 *>(smem + S::L2_OFF + qo + auxo);
       }
-#pragma unroll
-      for (int i = 0; i < 16; ++i) sa[i] = 0.f, pa[i] = 0.f;
-      const char *qt = st + S::Q_OFF + 32 * qb * ROWB, *dot = st + S::DO_OFF + 32 * qb * ROWB;
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
-        sa = mfma32(lds_read8(qt + qoff[s]), kf[s], sa);
-        pa = mfma32(lds_read8(dot + qoff[s]), vf[s], pa);
+        const bf16x8 qf = lds_read8(smem + QT + qoff[s]), df = lds_read8(smem + DOT + qoff[s]);
+        if (s == 0) {
+          mfma32_v_first(sa, qf, kf[0]);
+          mfma32_v_first(pa, df, vf[0]);
+        } else {
+          mfma32_v(sa, qf, kf[s]);
+          mfma32_v(pa, df, vf[s]);
+        }
       }
+      mfma_settle(sa, pa);
       uint32_t pw[8], dw[8];
-      // only sub-blocks that straddle the diagonal for this wave's keys need the mask
-      const int sub_min_pos = *reinterpret_cast<const int *>(st + S::POS_OFF + (32 * qb) * 4);
-      if (sub_min_pos >= u.key_pos0 + kw0 + 31) {
 #pragma unroll
-        for (int i = 0; i < 16; i += 2) {
-          const float p0 = fast_exp2(fmaf(sa[i], c, -l2v[i >> 2][i & 3]));
-          const float p1 = fast_exp2(fmaf(sa[i + 1], c, -l2v[i >> 2][(i & 3) + 1]));
-          pw[i >> 1] = pack_bf16(p0, p1);
-          dw[i >> 1] = pack_bf16(p0 * (pa[i] + ndv[i >> 2][i & 3]), p1 * (pa[i + 1] + ndv[i >> 2][(i & 3) + 1]));
-        }
-      } else {
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int4 pv = *reinterpret_cast<const int4 *>(smem + S::POS_OFF + (32 * qb + 8 * i4) * 4 + auxo);
+        const int pos4[4] = {pv.x, pv.y, pv.z, pv.w};
+        float p[4];
 #pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const int4 pv = *reinterpret_cast<const int4 *>(st + S::POS_OFF + (32 * qb + 8 * i4 + 4 * g) * 4);
-          const int pos4[4] = {pv.x, pv.y, pv.z, pv.w};
-          float p[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            p[e] = key_pos <= pos4[e] ? fast_exp2(fmaf(sa[4 * i4 + e], c, -l2v[i4][e])) : 0.f;
-          pw[2 * i4] = pack_bf16(p[0], p[1]);
-          pw[2 * i4 + 1] = pack_bf16(p[2], p[3]);
-          dw[2 * i4] = pack_bf16(p[0] * (pa[4 * i4] + ndv[i4][0]), p[1] * (pa[4 * i4 + 1] + ndv[i4][1]));
-          dw[2 * i4 + 1] = pack_bf16(p[2] * (pa[4 * i4 + 2] + ndv[i4][2]), p[3] * (pa[4 * i4 + 3] + ndv[i4][3]));
-        }
+        for (int e = 0; e < 4; ++e)
+          p[e] = key_pos <= pos4[e] ? fast_exp2(fmaf(sa[4 * i4 + e], c, -l2v[i4][e])) : 0.f;
+        pw[2 * i4] = pack_bf16(p[0], p[1]);
+        pw[2 * i4 + 1] = pack_bf16(p[2], p[3]);
+        dw[2 * i4] = pack_bf16(p[0] * (pa[4 * i4] + ndv[i4][0]), p[1] * (pa[4 * i4 + 1] + ndv[i4][1]));
+        dw[2 * i4 + 1] = pack_bf16(p[2] * (pa[4 * i4 + 2] + ndv[i4][2]), p[3] * (pa[4 * i4 + 3] + ndv[i4][3]));
       }
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const bf16x8 pb = __builtin_bit_cast(bf16x8, u32x4{pw[4 * t], pw[4 * t + 1], pw[4 * t + 2], pw[4 * t + 3]});
         const bf16x8 db = __builtin_bit_cast(bf16x8, u32x4{dw[4 * t], dw[4 * t + 1], dw[4 * t + 2], dw[4 * t + 3]});
-        const int ro = 16 * t * ROWB;
+        const int ro = t * HALF;
 #pragma unroll
         for (int b = 0; b < NDB; ++b) {
-          const bf16x8 dot_t = join(lds_read_tr4(dot + toff[0][b] + ro), lds_read_tr4(dot + toff[1][b] + ro));
+          const bf16x8 dot_t = join(lds_read_tr4(smem + DOT + ro + toff[0][b]), lds_read_tr4(smem + DOT + ro + toff[1][b]));
           acc_dv[b] = mfma32(dot_t, pb, acc_dv[b]);
-          const bf16x8 q_t = join(lds_read_tr4(qt + toff[0][b] + ro), lds_read_tr4(qt + toff[1][b] + ro));
+          const bf16x8 q_t = join(lds_read_tr4(smem + QT + ro + toff[0][b]), lds_read_tr4(smem + QT + ro + toff[1][b]));
           acc_dk[b] = mfma32(q_t, db, acc_dk[b]);
         }
       }
     }
+    barrier_nofence();  // everybody is done with this stage
+    issue_next();       // block it+3 into it
+    advance_stage();
   }
+  wait_vmcnt<0>();  // nothing may still be writing LDS when the workgroup ends
 
   // ---- write dK (scaled) and dV of the wave's 32 keys
   if (kw0 + r < u.n_valid) {

@@ -142,6 +142,35 @@ __device__ __forceinline__ void pin(bf16x8 &v) {
   asm volatile("" : "+v"(w));
   v = __builtin_bit_cast(bf16x8, w);
 }
+// same, but leaves the value in an accumulation register (MFMA A/B operands can be read from either file;
+// values only ever consumed by MFMAs need not occupy architectural VGPRs)
+__device__ __forceinline__ void pin_acc(bf16x8 &v) {
+  u32x4 w = __builtin_bit_cast(u32x4, v);
+  asm volatile("" : "+a"(w));
+  v = __builtin_bit_cast(bf16x8, w);
+}
+
+// MFMA whose result tuple lives in ARCHITECTURAL registers and whose B operand lives in the accumulation file.
+// A kernel that runs one wave per SIMD has 256 registers of each kind; once it needs both, the compiler gives
+// every MFMA an accumulation-file result, and a result the vector ALU needs next then costs one v_accvgpr_read per
+// register.  These forms are for short-lived score tiles that go straight to the vector ALU, with B operands that
+// stay resident for the whole kernel and are read by MFMAs only.
+// The compiler does not see an MFMA in them, so it inserts none of the wait states the hardware requires between an
+// MFMA and a non-MFMA instruction that reads its result: mfma_settle() supplies them (the result of this 8-pass
+// MFMA may be read 11 issue slots after it; 12 are waited) and takes the tuples as operands, so no reader can be
+// scheduled ahead of it.  Between the first MFMA of a chain and the settle nothing else may touch the tuple.
+// Dependent MFMAs on one tuple need no wait.
+__device__ __forceinline__ void mfma32_v_first(f32x16 &d, bf16x8 a, bf16x8 b_acc) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0"
+               : "=&v"(d)
+               : "v"(__builtin_bit_cast(u32x4, a)), "a"(__builtin_bit_cast(u32x4, b_acc)));
+}
+__device__ __forceinline__ void mfma32_v(f32x16 &d, bf16x8 a, bf16x8 b_acc) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
+               : "+v"(d)
+               : "v"(__builtin_bit_cast(u32x4, a)), "a"(__builtin_bit_cast(u32x4, b_acc)));
+}
+__device__ __forceinline__ void mfma_settle(f32x16 &x, f32x16 &y) { asm volatile("s_nop 11" : "+v"(x), "+v"(y)); }
 __device__ __forceinline__ void pin(float &v) { asm volatile("" : "+v"(v)); }
 __device__ __forceinline__ void pin(int &v) { asm volatile("" : "+v"(v)); }
 

@@ -27,6 +27,7 @@ struct FwdUnit {  // one (q tile, q head)
 struct BwdUnit {  // one (KV tile, KV head)
   int32_t slot_begin;  // first slot of the first q block that sees this KV tile
   int32_t slot_end;    // end of the document's slots
+  int32_t slot_full;   // first q block (slot index) from which every slot sees all keys of the tile
   int32_t kv_row;      // packed KV row of the tile's first key
   int32_t n_valid;     // valid keys in the tile
   int32_t key_pos0;    // document position of the tile's first key

@@ -156,7 +156,7 @@ void schedule(ca_plan_t *p) {
     const int32_t cover = last_pos + 1;
     const int32_t doc_len = int32_t(p->doc_kv_len[dd]);
     for (int32_t k0 = 0; k0 < doc_len; k0 += BWD_BN) {
-      BwdUnit u{int32_t(s1), int32_t(s1), kv_row0 + k0, std::min<int32_t>(BWD_BN, doc_len - k0), k0, 0};
+      BwdUnit u{int32_t(s1), int32_t(s1), int32_t(s1), kv_row0 + k0, std::min<int32_t>(BWD_BN, doc_len - k0), k0, 0};
       if (k0 < cover) {
         // first slot whose position can see key k0
         const int32_t *b = p->slot_pos.data() + s0, *e = p->slot_pos.data() + s1;
@@ -166,6 +166,10 @@ void schedule(ca_plan_t *p) {
         while (end - BWD_BQ >= s0 + first && p->slot_row[end - BWD_BQ] < 0) end -= BWD_BQ;  // drop pure-padding blocks
         u.slot_begin = int32_t(s0 + first);
         u.slot_end = int32_t(end);
+        // blocks from here on lie entirely below the diagonal of this tile: no mask needed
+        int64_t full = std::lower_bound(b, e, k0 + BWD_BN - 1) - b;
+        full = (full + BWD_BQ - 1) / BWD_BQ * BWD_BQ;
+        u.slot_full = int32_t(std::min<int64_t>(std::max<int64_t>(s0 + full, u.slot_begin), end));
       }
       btiles.push_back(u);
     }

@@ -125,8 +125,12 @@ def check_schedule(b):
     assert np.all(np.diff(span) <= 0), "longest first"
     key_cover = np.zeros((b.total_kv, b.n_kv_heads), np.int32)
     docs_with_tasks = sorted(set(b.task_doc.tolist()))
-    for i, (sb, se, kvrow, nvalid, kp0, hk) in enumerate(bu.tolist()):
+    for i, (sb, se, sf, kvrow, nvalid, kp0, hk) in enumerate(bu.tolist()):
         assert i % b.n_kv_heads == hk and 1 <= nvalid <= bn and (se - sb) % bq == 0 and se >= sb
+        assert sb <= sf <= se and (sf - sb) % bq == 0
+        assert np.all(pos[sf:se] >= kp0 + bn - 1), "blocks from slot_full on see every key of the tile"
+        if sf - bq >= sb:
+            assert pos[sf - bq] < kp0 + bn - 1, "slot_full is the first such block"
         key_cover[kvrow:kvrow + nvalid, hk] += 1
         dd = [d for d in docs_with_tasks if b.doc_kv_start[d] <= kvrow < b.doc_kv_start[d] + b.doc_kv_len[d]][0]
         assert kvrow - b.doc_kv_start[dd] == kp0
