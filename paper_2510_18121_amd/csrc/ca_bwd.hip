@@ -220,7 +220,7 @@ __global__ __launch_bounds__(512, 2) void ca_bwd_dq_kernel(const FwdUnit *__rest
 // ------------------------------------------------------------------------------------------------ dK, dV
 template <int D>
 struct DkvSmem {
-  static constexpr int NST = 3;
+  static constexpr int NST = 4;
   static constexpr int TILE = BWD_BQ * 2 * D;       // one Q or dO tile of 64 slots
   static constexpr int Q_OFF = 0;
   static constexpr int DO_OFF = TILE;
@@ -251,6 +251,7 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   constexpr int PFB = (2 * PA) / (2 * NDB);  // natural fragments fetched per gradient MFMA pair
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(CA_LDS char *)smem;  // LDS byte address of the dynamic segment
   const BwdUnit u = units[blockIdx.x];
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, r = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -280,6 +281,8 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   // the direct loads) while the previous block was being issued.  Past the last block the cursor stays on it:
   // every iteration issues the same number of loads, which keeps the s_waitcnt bookkeeping constant.
   int pblk = n_blocks - 1, ph = 0, pst = 0;
+  uint32_t pst_addr = lds0;  // LDS address of the stage being filled
+  const char *q_head = reinterpret_cast<const char *>(Q), *do_head = reinterpret_cast<const char *>(dO);  // + head ph
   int rown[RPW];
   uint64_t rowoff[NLD];
   const uint32_t row_bytes = uint32_t(Hq) * D * 2;
@@ -304,42 +307,56 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
       rowoff[n] = uint64_t(uint32_t(max(row, 0))) * row_bytes + uint32_t((hk * G * D + ld_coff[n]) * 2);
     }
   };
-  auto issue_next = [&]() __attribute__((always_inline)) {
-    char *st = smem + pst * S::STAGE;
-    const uint32_t hoff = uint32_t(ph) * D * 2;
-    const char *qb = reinterpret_cast<const char *>(Q) + hoff, *dob = reinterpret_cast<const char *>(dO) + hoff;
-#pragma unroll
-    for (int n = 0; n < NLD; ++n) {
-      load_lds16(qb + rowoff[n], st + S::Q_OFF + (RPW * wave + RPI * n) * ROWB);
-      load_lds16(dob + rowoff[n], st + S::DO_OFF + (RPW * wave + RPI * n) * ROWB);
+  constexpr int LPI = 2 * NLD + 1;  // loads per wave per iteration
+  // The loads of one (block, head) come in LPI pieces, so that the pipelined path can hand them to the memory
+  // pipeline a few at a time between its MFMAs (a burst of LPI loads from all four waves at once stalls the
+  // issuing waves for hundreds of cycles).  The last piece moves the cursor.
+  auto issue_piece = [&](int i) __attribute__((always_inline)) {
+    if (i < 2 * NLD) {
+      const int n = i >> 1;
+      load_lds16_at(((i & 1) ? do_head : q_head) + rowoff[n], pst_addr + ((i & 1) ? S::DO_OFF : S::Q_OFF) + (RPW * wave + RPI * n) * ROWB);
+      return;
     }
     const int s0 = u.slot_begin + pblk * BWD_BQ, h = hk * G + ph;
     const float *aux = wave == 0 ? l2_slot + int64_t(h) * padded + s0
                      : wave == 1 ? delta_slot + int64_t(h) * padded + s0
                                  : reinterpret_cast<const float *>(slot_pos) + s0;
-    char *ad = st + (wave == 0 ? S::L2_OFF : wave == 1 ? S::DL_OFF : wave == 2 ? S::POS_OFF : S::SPARE_OFF);
-    load_lds4(aux + lane, ad);
+    load_lds4_at(aux + lane, pst_addr + (wave == 0 ? S::L2_OFF : wave == 1 ? S::DL_OFF : wave == 2 ? S::POS_OFF : S::SPARE_OFF));
     pst = pst + 1 == NST ? 0 : pst + 1;
+    pst_addr = pst == 0 ? lds0 : pst_addr + S::STAGE;
+    q_head += D * 2, do_head += D * 2;
     if (++ph == G) {
       if (pblk > 0) {
         ph = 0;
+        q_head -= G * D * 2, do_head -= G * D * 2;
         --pblk;
         make_rowoff();                      // from the indices fetched G iterations ago
         if (pblk > 0) load_rows(pblk - 1);  // for the block after this one
       } else {
         ph = G - 1;  // past the end: keep re-fetching the final (block, head)
+        q_head -= D * 2, do_head -= D * 2;
       }
     }
   };
-  constexpr int LPI = 2 * NLD + 1;  // loads per wave per iteration
+  auto issue_next = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < LPI; ++i) issue_piece(i);
+  };
+  // plain load pieces handed out per phase of the pipelined path after its barrier: second half of B(2 it + 1),
+  // A(2 it + 2), B(2 it + 2), A(2 it + 3); the cursor piece follows the last one
+  constexpr int NB1 = D == 128 ? 2 : 1, NA0 = D == 128 ? 3 : 1, NB0 = D == 128 ? 3 : 1;
+  constexpr int NA1 = LPI - 1 - NB1 - NA0 - NB0;
+  constexpr int LP1 = NB1;  // pieces of the newest block that are issued before the pipelined path takes over
 
   if (n_it > 0) {
     load_rows(pblk);
     make_rowoff();
     if (pblk > 0) load_rows(pblk - 1);
-    issue_next();  // blocks 0, 1, 2: three ahead
+    issue_next();  // blocks 0 .. 3: four ahead; the last one is completed further down
     issue_next();
     issue_next();
+#pragma unroll
+    for (int i = 0; i < LP1; ++i) issue_piece(i);
   }
 
   // resident K, V fragments of the wave's 32 keys (B operands of S = Q K^T and dP = dO V^T).  Keys past the
@@ -356,13 +373,13 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   }
   int qoff[NS];  // natural fragment s of tile row r (second sub-block: + 32 rows)
 #pragma unroll
-  for (int s = 0; s < NS; ++s) qoff[s] = tile_off<D>(r, 2 * s + g);
+  for (int s = 0; s < NS; ++s) qoff[s] = lds0 + tile_off<D>(r, 2 * s + g);
   int toff[2][NDB];
 #pragma unroll
   for (int h2 = 0; h2 < 2; ++h2)
 #pragma unroll
     for (int b = 0; b < NDB; ++b)
-      toff[h2][b] = tile_off<D>(4 * g + (li >> 2) + 8 * h2, 4 * b + 2 * dh + ((li >> 1) & 1)) + 8 * (li & 1);
+      toff[h2][b] = lds0 + tile_off<D>(4 * g + (li >> 2) + 8 * h2, 4 * b + 2 * dh + ((li >> 1) & 1)) + 8 * (li & 1);
 
   f32x16 acc_dk[NDB], acc_dv[NDB];
 #pragma unroll
@@ -378,156 +395,227 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   barrier_nofence();
 
   // ------------------------------------------------------------------------------------------------
-  // Pipelined path for blocks entirely below the diagonal.  With one wave per SIMD nothing hides an LDS
-  // latency except this wave's own MFMAs, so every MFMA finds its LDS operand already in registers:
-  //   * score phase (S, dP: 2 NS MFMAs): natural Q/dO fragments, held PA k-steps ahead and re-fetched as they
-  //     are consumed; meanwhile the first half of the transposed fragments of this sub-block is fetched;
-  //   * vector phase: P = exp2(c S - L2), dS = P (dP - Delta), packed to bf16;
-  //   * gradient phase (dV, dK: 4 NDB MFMAs): transposed dO/Q fragments, second half re-fetched into the
-  //     registers of the first as it is consumed; meanwhile the natural fragments of the NEXT sub-block are
-  //     fetched.
-  // sched_barrier fences pin that order.  The barrier for the next block sits in the middle of the last gradient
-  // phase of an iteration: after it no wave reads this iteration's LDS stage any more (the rest of the phase works
-  // from registers), so the stage can be refilled at once, three blocks ahead with three stages.
-  bf16x8 opq[PA], opd[PA];  // natural fragments, k-steps s .. s+PA-1 of the sub-block in flight
+  // Pipelined path for blocks entirely below the diagonal.  With one wave per SIMD nothing hides a latency except
+  // this wave's own instructions, so the sub-blocks k = 0, 1, .. (two per query block) are software-pipelined and
+  // the matrix pipe, the vector ALU, the LDS and the memory pipeline all get their work a little at a time:
+  //   phase A(k): the score MFMAs of sub-block k+1 (S and dP - Delta: 2 NS MFMAs into architectural registers; the
+  //               dP chain starts from -Delta as its C operand); between them P = exp2(c S - L2) of sub-block k.
+  //               Natural Q/dO fragments are held PA k-steps ahead and re-fetched as they are consumed; the first
+  //               half of the transposed fragments of sub-block k is fetched meanwhile.
+  //   phase B(k): the gradient MFMAs of sub-block k in the order dV, dK (query rows 0..15), dV, dK (rows 16..31);
+  //               dS = P (dP - Delta) is formed during the first dV group.  The second half of the transposed
+  //               fragments replaces the first as it is consumed; the first natural fragments of sub-block k+2,
+  //               L2 of sub-block k+1 and -Delta of sub-block k+2 are fetched meanwhile.
+  // sched_barrier fences pin that order.  Block it+1 is read from phase B of block it's first sub-block on, so the
+  // workgroup barrier in the middle of the last phase B of block it-1 (after which nobody reads block it-1's stage
+  // any more: the rest of the phase works from registers) waits until block it+1 has landed, and the loads of block
+  // it+3 into the stage it frees are handed out one at a time over the following phases: four stages, at most
+  // two blocks in flight.
+  bf16x8 opq[PA], opd[PA];  // natural fragments, k-steps s .. s+PA-1 of the score chain in flight
   bf16x8 opb[2 * NDB];      // transposed fragments: [2b] = dO^T, [2b+1] = Q^T of column block b
-  // qoff / toff / auxo are kept as byte offsets into the CURRENT stage and advanced once per iteration, so that
-  // every LDS read is (loop-carried register) + (immediate).
-  int auxo = 16 * g;
-  int stage = 0;
-  auto advance_stage = [&]() __attribute__((always_inline)) {
-    const int adv = stage == NST - 1 ? -(NST - 1) * S::STAGE : S::STAGE;
-    stage = stage == NST - 1 ? 0 : stage + 1;
+  // qoff / auxq (natural reads and row statistics of the score chain) and toff / auxo (transposed reads, row
+  // statistics of the vector work) are byte offsets into a stage, advanced once per block, so that every LDS read
+  // is (loop-carried register) + (immediate).  In the pipelined path the first pair runs one stage ahead of the
+  // second for part of the time.
+  int auxo = lds0 + 16 * g, auxq = auxo;
+  int stage = 0, qstage = 0;
+  auto advance_q = [&]() __attribute__((always_inline)) {
+    const int adv = qstage == NST - 1 ? -(NST - 1) * S::STAGE : S::STAGE;
+    qstage = qstage == NST - 1 ? 0 : qstage + 1;
 #pragma unroll
     for (int s = 0; s < NS; ++s) qoff[s] += adv;
+    auxq += adv;
+  };
+  auto advance_t = [&]() __attribute__((always_inline)) {
+    const int adv = stage == NST - 1 ? -(NST - 1) * S::STAGE : S::STAGE;
+    stage = stage == NST - 1 ? 0 : stage + 1;
 #pragma unroll
     for (int b = 0; b < NDB; ++b) toff[0][b] += adv, toff[1][b] += adv;
     auxo += adv;
   };
   constexpr int SUB = 32 * ROWB, HALF = 16 * ROWB;
-  if (n_fast > 0) {
-#pragma unroll
-    for (int s = 0; s < PA; ++s) {
-      opq[s] = lds_read8(smem + S::Q_OFF + qoff[s]);
-      opd[s] = lds_read8(smem + S::DO_OFF + qoff[s]);
-    }
-  }
+  static_assert(NA1 >= 0 && NA1 <= NS / 2 && NA0 <= NS / 2 && NB0 <= 4 && NB1 <= 2, "piece schedule");
   int it = 0;
-  for (; it < n_fast; ++it) {
+  if (n_fast > 0) {
+    f32x16 sc[2], dp[2];  // score tiles S and dP - Delta of sub-blocks k (even: [0], odd: [1])
+    f32x16 ndt;           // -Delta of the 16 query rows of this lane (C operand layout), for the next dP chain
+    f32x4 l2v[4];         // log2e*LSE of the 16 query rows of this lane, sub-block k
+    uint32_t pw[8], dw[8];  // P and dS of sub-block k, packed
+    float pv[16];           // P of sub-block k
+    auto load_l2 = [&](int off) __attribute__((always_inline)) {
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      const int QT = S::Q_OFF + qb * SUB, DOT = S::DO_OFF + qb * SUB;  // sub-block tiles inside the stage
-      f32x16 sa, pa;
-      // ---- score phase
+      for (int i4 = 0; i4 < 4; ++i4) l2v[i4] = lds_ld<f32x4>(S::L2_OFF + off + 32 * i4);
+    };
+    auto load_nd = [&](int off) __attribute__((always_inline)) {
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const f32x4 x = lds_ld<f32x4>(S::DL_OFF + off + 32 * i4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ndt[4 * i4 + e] = x[e];
+      }
+    };
+    // P of query rows 4 i4 + 2 h, + 1 of this lane's 16 (h = 0, 1): half a group of four
+    auto vec_p = [&](const f32x16 &sa, int i4, int h) __attribute__((always_inline)) {
+#pragma unroll
+      for (int e = 2 * h; e < 2 * h + 2; ++e) pv[4 * i4 + e] = fast_exp2(fmaf(sa[4 * i4 + e], c, -l2v[i4][e]));
+      pw[2 * i4 + h] = pack_bf16(pv[4 * i4 + 2 * h], pv[4 * i4 + 2 * h + 1]);
+    };
+    auto vec_ds = [&](const f32x16 &da, int i4) __attribute__((always_inline)) {
+      dw[2 * i4] = pack_bf16(pv[4 * i4] * da[4 * i4], pv[4 * i4 + 1] * da[4 * i4 + 1]);
+      dw[2 * i4 + 1] = pack_bf16(pv[4 * i4 + 2] * da[4 * i4 + 2], pv[4 * i4 + 3] * da[4 * i4 + 3]);
+    };
+    // Score chain of one sub-block into (sw, dpw); nat = offset of its natural tiles from qoff's stage.  With VEC,
+    // P of (sr) is formed between the MFMAs, and the transposed first-half fragments of the sub-block at offset
+    // `tro` of toff's stage are fetched.  Load pieces piece0 .. piece0 + np - 1 go out at the odd steps.
+    auto phase_a = [&](f32x16 &sw, f32x16 &dpw, const f32x16 &sr, int nat, int tro, bool vec, int piece0, int np,
+                       bool cursor_piece) __attribute__((always_inline)) {
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
-        if (s == 0) {
-          mfma32_v_first(sa, opq[0], kf[0]);
-          mfma32_v_first(pa, opd[0], vf[0]);
-        } else {
-          mfma32_v(sa, opq[s % PA], kf[s]);
-          mfma32_v(pa, opd[s % PA], vf[s]);
+        // every MFMA is followed by its share of the other work, so that the next one finds the matrix pipe free
+        if (s == 0) mfma32_v_first(sw, opq[0], kf[0]);
+        else mfma32_v(sw, opq[s % PA], kf[s]);
+        if (vec) {
+          const int X = ((s & 1) ? S::Q_OFF : S::DO_OFF) + tro;
+          opb[s] = join(lds_read_tr4_at(X + toff[0][s >> 1]), lds_read_tr4_at(X + toff[1][s >> 1]));
+          if constexpr (NS == 8) {
+            vec_p(sr, s >> 1, s & 1);
+          } else {
+            vec_p(sr, s, 0);
+          }
         }
+        __builtin_amdgcn_sched_barrier(0);
+        if (s == 0) mfma32_v_first(dpw, opd[0], vf[0], ndt);
+        else mfma32_v(dpw, opd[s % PA], vf[s]);
         if (s + PA < NS) {
-          opq[s % PA] = lds_read8(smem + QT + qoff[s + PA]);
-          opd[s % PA] = lds_read8(smem + DOT + qoff[s + PA]);
+          // dO before Q: the S MFMA that comes first waits for the younger of the two reads, which covers both
+          opd[s % PA] = lds_read8_at(S::DO_OFF + nat + qoff[s + PA]);
+          opq[s % PA] = lds_read8_at(S::Q_OFF + nat + qoff[s + PA]);
         }
-        {  // transposed fragment s of the first half (rows 0..15 of the sub-block)
-          const int X = (s & 1) ? QT : DOT;
-          opb[s] = join(lds_read_tr4(smem + X + toff[0][s >> 1]), lds_read_tr4(smem + X + toff[1][s >> 1]));
+        if ((s & 1) && (s >> 1) < np) issue_piece(piece0 + (s >> 1));
+        if (vec) {
+          if constexpr (NS != 8) vec_p(sr, s, 1);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
-      // ---- vector phase (the auxiliary reads travel while the last MFMA drains)
-      f32x4 ndv[4], l2v[4];
+      mfma_settle(sw, dpw, ndt);
+      if (cursor_piece) issue_piece(LPI - 1);  // the piece with the cursor's branches stays outside the chain
+    };
+
+    // blocks 0 and 1 have landed (this wave's part); block 2 and the issued part of block 3 may be in flight
+    wait_vmcnt<LPI + LP1>();
+    barrier_nofence();
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const int qo = (32 * qb + 8 * i4) * 4;
-        ndv[i4] = *reinterpret_cast<const f32x4 *>(smem + S::DL_OFF + qo + auxo);
-        l2v[i4] = *reinterpret_cast<const f32x4 *>(smem + S::L2_OFF + qo + auxo);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_settle(sa, pa);
-      uint32_t pw[8], dw[8];
+    for (int s = 0; s < PA; ++s) {
+      opd[s] = lds_read8_at(S::DO_OFF + qoff[s]);
+      opq[s] = lds_read8_at(S::Q_OFF + qoff[s]);
+    }
+    load_nd(auxq);
+    phase_a(sc[0], dp[0], sc[0], 0, 0, false, 0, 0, false);
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        float p[4];
+    for (int s = 0; s < PA; ++s) {
+      opd[s] = lds_read8_at(S::DO_OFF + SUB + qoff[s]);
+      opq[s] = lds_read8_at(S::Q_OFF + SUB + qoff[s]);
+    }
+    load_l2(auxo);
+    load_nd(auxq + 32 * 4);
+
+    for (; it < n_fast; ++it) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) p[e] = fast_exp2(fmaf(sa[4 * i4 + e], c, -l2v[i4][e]));
-        pw[2 * i4] = pack_bf16(p[0], p[1]);
-        pw[2 * i4 + 1] = pack_bf16(p[2], p[3]);
-        dw[2 * i4] = pack_bf16(p[0] * (pa[4 * i4] + ndv[i4][0]), p[1] * (pa[4 * i4 + 1] + ndv[i4][1]));
-        dw[2 * i4 + 1] = pack_bf16(p[2] * (pa[4 * i4 + 2] + ndv[i4][2]), p[3] * (pa[4 * i4 + 3] + ndv[i4][3]));
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      // ---- gradient phase
+      for (int qb = 0; qb < 2; ++qb) {
+        // ---- phase A: scores of the next sub-block (the other half of this block, or the first half of the
+        // next block), P of this one
+        if (qb == 0) phase_a(sc[1], dp[1], sc[0], SUB, 0, true, NB1, NA0, false);
+        else phase_a(sc[0], dp[0], sc[1], 0, SUB, true, NB1 + NA0 + NB0, NA1, true);
+        if (qb == 0) advance_q();  // natural reads and chain statistics now address block it+1
+        // ---- phase B
+        const int QT = S::Q_OFF + qb * SUB, DOT = S::DO_OFF + qb * SUB;  // this sub-block's tiles inside the stage
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        if (qb == 1 && t == 1) {
-          // All LDS reads of this iteration's stage have been issued (the transposed second half just above);
-          // block it+1 has landed (this wave's part): only block it+2 may be in flight.
-          wait_vmcnt<LPI>();
-          barrier_nofence();  // waits for this wave's LDS reads, then for everybody
-          issue_next();       // block it+3 into the stage of block it
-          advance_stage();    // the offsets now address block it+1
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        const bf16x8 pb = __builtin_bit_cast(bf16x8, u32x4{pw[4 * t], pw[4 * t + 1], pw[4 * t + 2], pw[4 * t + 3]});
-        const bf16x8 db = __builtin_bit_cast(bf16x8, u32x4{dw[4 * t], dw[4 * t + 1], dw[4 * t + 2], dw[4 * t + 3]});
-#pragma unroll
-        for (int b = 0; b < NDB; ++b) {
-          acc_dv[b] = mfma32(opb[2 * b], pb, acc_dv[b]);
-          acc_dk[b] = mfma32(opb[2 * b + 1], db, acc_dk[b]);
-          if (t == 0) {  // second half of this sub-block (rows 16..31) into the registers just consumed
-            opb[2 * b] = join(lds_read_tr4(smem + DOT + HALF + toff[0][b]), lds_read_tr4(smem + DOT + HALF + toff[1][b]));
-            opb[2 * b + 1] = join(lds_read_tr4(smem + QT + HALF + toff[0][b]), lds_read_tr4(smem + QT + HALF + toff[1][b]));
+        for (int t = 0; t < 2; ++t) {
+          if (qb == 1 && t == 1) {
+            // All LDS reads of block it's stage have been issued (the transposed second halves just above).
+            // Block it+2 must have landed (this wave's part): only block it+3 may be in flight.
+            wait_vmcnt<LPI>();
+            barrier_nofence();  // waits for this wave's LDS reads, then for everybody
+            advance_t();        // transposed reads and vector statistics now address block it+1
+            __builtin_amdgcn_sched_barrier(0);
           }
-          // natural fragments of the next sub-block: second half of this stage for qb == 0 (spread over both
-          // halves of the phase), first half of the next stage for qb == 1 (only after the barrier)
-          if (qb == 0) {
 #pragma unroll
-            for (int x = 0; x < PFB; ++x) {
-              const int o = (t * NDB + b) * PFB + x, sn = o >> 1;
-              if (o & 1) opd[sn] = lds_read8(smem + S::DO_OFF + SUB + qoff[sn]);
-              else opq[sn] = lds_read8(smem + S::Q_OFF + SUB + qoff[sn]);
-            }
-          } else if (t == 1) {
+          for (int w = 0; w < 2; ++w) {  // w = 0: dV group, w = 1: dK group
 #pragma unroll
-            for (int x = 0; x < 2 * PFB; ++x) {
-              const int o = b * 2 * PFB + x, sn = o >> 1;
-              if (o & 1) opd[sn] = lds_read8(smem + S::DO_OFF + qoff[sn]);
-              else opq[sn] = lds_read8(smem + S::Q_OFF + qoff[sn]);
+            for (int b = 0; b < NDB; ++b) {
+              const int m = (2 * t + w) * NDB + b;  // MFMA number inside the phase
+              if (w == 0) {
+                const bf16x8 pb =
+                    __builtin_bit_cast(bf16x8, u32x4{pw[4 * t], pw[4 * t + 1], pw[4 * t + 2], pw[4 * t + 3]});
+                acc_dv[b] = mfma32(opb[2 * b], pb, acc_dv[b]);
+                if (t == 0)  // rows 16..31 of this sub-block into the registers just consumed
+                  opb[2 * b] = join(lds_read_tr4_at(DOT + HALF + toff[0][b]), lds_read_tr4_at(DOT + HALF + toff[1][b]));
+              } else {
+                const bf16x8 db =
+                    __builtin_bit_cast(bf16x8, u32x4{dw[4 * t], dw[4 * t + 1], dw[4 * t + 2], dw[4 * t + 3]});
+                acc_dk[b] = mfma32(opb[2 * b + 1], db, acc_dk[b]);
+                if (t == 0)
+                  opb[2 * b + 1] = join(lds_read_tr4_at(QT + HALF + toff[0][b]), lds_read_tr4_at(QT + HALF + toff[1][b]));
+              }
+              // dS of this sub-block, during the first dV group
+              if (t == 0 && w == 0) {
+#pragma unroll
+                for (int i4 = (4 * b) / NDB; i4 < (4 * (b + 1)) / NDB; ++i4) vec_ds(dp[qb], i4);
+              }
+              // first natural fragments of sub-block k+2 (block it+1: first half for qb == 0, second for qb == 1)
+#pragma unroll
+              for (int o = (2 * PA * m) / (4 * NDB); o < (2 * PA * (m + 1)) / (4 * NDB); ++o) {
+                const int sn = o >> 1;
+                if (o & 1) opq[sn] = lds_read8_at(S::Q_OFF + qb * SUB + qoff[sn]);
+                else opd[sn] = lds_read8_at(S::DO_OFF + qb * SUB + qoff[sn]);
+              }
+              // load pieces: the block that the barrier has just made room for (qb == 1), and more of it one
+              // phase later (qb == 0)
+              if (b == NDB - 1) {
+                const int grp = 2 * t + w;
+                if (qb == 1 && t == 1 && w < NB1) issue_piece(w);
+                if (qb == 0 && grp < NB0) issue_piece(NB1 + NA0 + grp);
+              }
+              __builtin_amdgcn_sched_barrier(0);
             }
           }
-          __builtin_amdgcn_sched_barrier(0);
+          // L2 of sub-block k+1 and -Delta of sub-block k+2 (the chain of sub-block k+1 has consumed its own)
+          if (t == 0) {
+            load_l2(qb == 0 ? auxo + 32 * 4 : auxq);
+            load_nd(qb == 0 ? auxq : auxq + 32 * 4);
+          }
         }
       }
     }
   }
 
+  if (n_it > 0) {  // complete the block whose first pieces were issued last
+#pragma unroll
+    for (int i = LP1; i < LPI; ++i) issue_piece(i);
+  }
   // ------------------------------------------------------------------------------------------------
   // General path: blocks that straddle the diagonal (mask, skip of invisible sub-blocks).  One barrier before
   // and one after the compute, then the refill of this stage.
   for (; it < n_it; ++it) {
-    wait_vmcnt<2 * LPI>();  // block `it` has landed (this wave's part); blocks it+1, it+2 may be in flight
+    wait_vmcnt<3 * LPI>();  // block `it` has landed (this wave's part); blocks it+1 .. it+3 may be in flight
     barrier_nofence();
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       const int QT = S::Q_OFF + qb * SUB, DOT = S::DO_OFF + qb * SUB;
       // sub-block entirely above the diagonal for this wave's keys? (slot positions are sorted)
-      const int sub_max_pos = *reinterpret_cast<const int *>(smem + stage * S::STAGE + S::POS_OFF + (32 * qb + 31) * 4);
+      const int sub_max_pos = lds_ld<int>(lds0 + stage * S::STAGE + S::POS_OFF + (32 * qb + 31) * 4);
       if (sub_max_pos < u.key_pos0 + kw0) continue;
       f32x16 sa, pa;
       f32x4 l2v[4], ndv[4];  // log2e*LSE and -Delta of this lane's 16 query rows
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
         const int qo = (32 * qb + 8 * i4) * 4;
-        ndv[i4] = *reinterpret_cast<const f32x4 *>(smem + S::DL_OFF + qo + auxo);
-        l2v[i4] = *reinterpret_cast<const f32x4 *>(smem + S::L2_OFF + qo + auxo);
+        ndv[i4] = lds_ld<f32x4>(S::DL_OFF + qo + auxo);
+        l2v[i4] = lds_ld<f32x4>(S::L2_OFF + qo + auxo);
       }
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
-        const bf16x8 qf = lds_read8(smem + QT + qoff[s]), df = lds_read8(smem + DOT + qoff[s]);
+        const bf16x8 qf = lds_read8_at(QT + qoff[s]), df = lds_read8_at(DOT + qoff[s]);
         if (s == 0) {
           mfma32_v_first(sa, qf, kf[0]);
           mfma32_v_first(pa, df, vf[0]);
@@ -540,8 +628,8 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
       uint32_t pw[8], dw[8];
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        const int4 pv = *reinterpret_cast<const int4 *>(smem + S::POS_OFF + (32 * qb + 8 * i4) * 4 + auxo);
-        const int pos4[4] = {pv.x, pv.y, pv.z, pv.w};
+        const u32x4 pv = lds_ld<u32x4>(S::POS_OFF + (32 * qb + 8 * i4) * 4 + auxo);
+        const int pos4[4] = {int(pv[0]), int(pv[1]), int(pv[2]), int(pv[3])};
         float p[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e)
@@ -558,16 +646,17 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
         const int ro = t * HALF;
 #pragma unroll
         for (int b = 0; b < NDB; ++b) {
-          const bf16x8 dot_t = join(lds_read_tr4(smem + DOT + ro + toff[0][b]), lds_read_tr4(smem + DOT + ro + toff[1][b]));
+          const bf16x8 dot_t = join(lds_read_tr4_at(DOT + ro + toff[0][b]), lds_read_tr4_at(DOT + ro + toff[1][b]));
           acc_dv[b] = mfma32(dot_t, pb, acc_dv[b]);
-          const bf16x8 q_t = join(lds_read_tr4(smem + QT + ro + toff[0][b]), lds_read_tr4(smem + QT + ro + toff[1][b]));
+          const bf16x8 q_t = join(lds_read_tr4_at(QT + ro + toff[0][b]), lds_read_tr4_at(QT + ro + toff[1][b]));
           acc_dk[b] = mfma32(q_t, db, acc_dk[b]);
         }
       }
     }
     barrier_nofence();  // everybody is done with this stage
-    issue_next();       // block it+3 into it
-    advance_stage();
+    issue_next();       // block it+4 into it
+    advance_q();
+    advance_t();
   }
   wait_vmcnt<0>();  // nothing may still be writing LDS when the workgroup ends
 
@@ -660,3 +749,4 @@ hipError_t launch_bwd(const ca_plan_t *p, const void *q, const void *k, const vo
 }
 
 }  // namespace ca
+

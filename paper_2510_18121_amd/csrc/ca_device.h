@@ -35,6 +35,17 @@ __device__ __forceinline__ bf16x4 lds_read_tr4(const char *p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CA_LDS bf16x4 *)(p));
 }
 
+// the same reads, addressed by a 32-bit LDS byte address (no generic-pointer arithmetic, and constant parts of
+// the address fold into the instruction's offset field)
+__device__ __forceinline__ bf16x8 lds_read8_at(uint32_t a) { return *(const CA_LDS bf16x8 *)a; }
+__device__ __forceinline__ bf16x4 lds_read_tr4_at(uint32_t a) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CA_LDS bf16x4 *)a);
+}
+template <class T>
+__device__ __forceinline__ T lds_ld(uint32_t a) {
+  return *(const CA_LDS T *)a;
+}
+
 __device__ __forceinline__ bf16x8 join(bf16x4 lo, bf16x4 hi) {
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
@@ -120,6 +131,19 @@ __device__ __forceinline__ void load_lds16_sbase(const void *base_uniform, uint3
                : "v"(lane_off), "s"(sb), "s"(m0v)
                : "memory", "m0");
 }
+// same, with the LDS destination given as a wave-uniform 32-bit LDS byte address
+__device__ __forceinline__ void load_lds16_at(const void *src, uint32_t lds_addr_uniform) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(src), "s"(lds_addr_uniform)
+               : "memory", "m0");
+}
+__device__ __forceinline__ void load_lds4_at(const void *src, uint32_t lds_addr_uniform) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+               :
+               : "v"(src), "s"(lds_addr_uniform)
+               : "memory", "m0");
+}
 __device__ __forceinline__ void load_lds4(const void *src, char *lds_base_uniform) {
   const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(CA_LDS char *)lds_base_uniform);
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
@@ -165,12 +189,23 @@ __device__ __forceinline__ void mfma32_v_first(f32x16 &d, bf16x8 a, bf16x8 b_acc
                : "=&v"(d)
                : "v"(__builtin_bit_cast(u32x4, a)), "a"(__builtin_bit_cast(u32x4, b_acc)));
 }
+// d = a b + c, with c another architectural tuple
+__device__ __forceinline__ void mfma32_v_first(f32x16 &d, bf16x8 a, bf16x8 b_acc, const f32x16 &c) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3"
+               : "=&v"(d)
+               : "v"(__builtin_bit_cast(u32x4, a)), "a"(__builtin_bit_cast(u32x4, b_acc)), "v"(c));
+}
 __device__ __forceinline__ void mfma32_v(f32x16 &d, bf16x8 a, bf16x8 b_acc) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
                : "+v"(d)
                : "v"(__builtin_bit_cast(u32x4, a)), "a"(__builtin_bit_cast(u32x4, b_acc)));
 }
 __device__ __forceinline__ void mfma_settle(f32x16 &x, f32x16 &y) { asm volatile("s_nop 11" : "+v"(x), "+v"(y)); }
+// same; `c` was the C operand of the chain's first MFMA: keeping it an operand here keeps its registers from being
+// reused (and overwritten by an LDS read in flight) while that MFMA may still be reading them
+__device__ __forceinline__ void mfma_settle(f32x16 &x, f32x16 &y, const f32x16 &c) {
+  asm volatile("s_nop 11" : "+v"(x), "+v"(y) : "v"(c));
+}
 __device__ __forceinline__ void pin(float &v) { asm volatile("" : "+v"(v)); }
 __device__ __forceinline__ void pin(int &v) { asm volatile("" : "+v"(v)); }
 
