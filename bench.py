@@ -20,6 +20,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 
+# HBM bytes per launch of the dK/dV kernel on workload 3, from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes whose
+# summary is profiles/hot_path_cfg3_hbm_traffic.md (counters scaled by the plain-copy calibration stated there)
+DKV_TRAFFIC_BYTES_CFG3 = int((74.8 + 0.50) * 2**30)
+
 
 def cpu_baseline(index: int):
     """The fp64 oracle, as it stands, timed on this host's cores on a bounded sample of the workload:
@@ -48,8 +52,8 @@ def cpu_baseline(index: int):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=3, help="1..5; 3 is the 8B-class 128K-token workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
@@ -116,6 +120,11 @@ def main():
         torch.cuda.synchronize()
 
     tflops = fl["total"] / (ms_per_step * 1e-3) / 1e12
+    bwd_ms = kavg["bwd_prep_ms"] + kavg["bwd_dkv_ms"] + kavg["bwd_dq_ms"]
+    bwd_tflops = fl["bwd"] / (bwd_ms * 1e-3) / 1e12 if bwd_ms > 0 else 0.0
+    clock_mhz = getattr(props, "clock_rate", 0) / 1e3
+    # 4096 dense bf16 flops per clock per CU; None when the runtime does not report the engine clock
+    peak_from_device = props.multi_processor_count * 4096 * clock_mhz * 1e6 / 1e12 if clock_mhz > 0 else None
     # the dK/dV kernel executes 4 of the backward's contractions (S, dP, dV, dK): 8*D*Hq*pairs flops
     dkv_flops = fl["bwd"] * 0.8
     bwd_main_tflops = dkv_flops / (kavg["bwd_dkv_ms"] * 1e-3) / 1e12 if kavg["bwd_dkv_ms"] > 0 else 0.0
@@ -129,12 +138,13 @@ def main():
                    "head_dim": b.head_dim, "docs": b.n_docs, "ca_tasks": b.n_tasks, "pairs": fl["pairs"],
                    "flops_fwd_bwd": fl["total"]},
         "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
-        "device": {"name": props.name, "cus": props.multi_processor_count,
-                   "clock_mhz": getattr(props, "clock_rate", 0) / 1e3},
-        "kernels_ms": kavg, "fwd_kernel_tflops": fwd_tflops, "plan_ms": plan_ms, "wall_s_timed": wall,
+        "device": {"name": props.name, "cus": props.multi_processor_count, "clock_mhz": clock_mhz,
+                   "peak_bf16_tflops_from_device": peak_from_device},
+        "kernels_ms": kavg, "fwd_only_tflops": fwd_tflops, "bwd_only_tflops": bwd_tflops, "plan_ms": plan_ms,
+        "wall_s_timed": wall,
         "roofline": {"kernel": "ca_bwd_dkv_kernel", "bound": "mfma", "achieved": bwd_main_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": bwd_main_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": None},
+                     "traffic": DKV_TRAFFIC_BYTES_CFG3 if args.workload == 3 else None},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload)

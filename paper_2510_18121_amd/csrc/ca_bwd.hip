@@ -63,9 +63,12 @@ template <int D>
 struct DqSmem {
   static constexpr int NST = 4;
   static constexpr int TILE = FWD_BN * 2 * D;
+  // a stage holds the K tile and then the V tile of one key block: both are reached from one address register
+  // through the 16-bit offset field of the LDS instructions
   static constexpr int K_OFF = 0;
-  static constexpr int V_OFF = NST * TILE;
-  static constexpr int TOTAL = 2 * NST * TILE;
+  static constexpr int V_OFF = TILE;
+  static constexpr int STAGE = 2 * TILE;
+  static constexpr int TOTAL = NST * STAGE;
 };
 
 template <int D>
@@ -83,6 +86,7 @@ __global__ __launch_bounds__(512, 2) void ca_bwd_dq_kernel(const FwdUnit *__rest
   constexpr int ROWB = 2 * D;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(CA_LDS char *)smem;  // LDS byte address of the dynamic segment
   const FwdUnit u = units[blockIdx.x];
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, r = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -115,7 +119,7 @@ __global__ __launch_bounds__(512, 2) void ca_bwd_dq_kernel(const FwdUnit *__rest
   auto issue_kv = [&](const char *src, int area, int tile) __attribute__((always_inline)) {
     const bool last = tile >= last_tile;
     const char *base = src + size_t(last ? last_tile : tile) * tile_bytes;
-    const uint32_t dst = uint32_t(area + (tile % NST) * S::TILE + 1024 * wave);
+    const uint32_t dst = lds0 + uint32_t(area + (tile % NST) * S::STAGE + 1024 * wave);
 #pragma unroll
     for (int n = 0; n < NLD; ++n) load_lds16_sbase(base, last ? ld_off_last[n] : ld_off[n], dst + 8192 * n);
   };
@@ -138,13 +142,13 @@ __global__ __launch_bounds__(512, 2) void ca_bwd_dq_kernel(const FwdUnit *__rest
   }
   int koff[NS];
 #pragma unroll
-  for (int s = 0; s < NS; ++s) koff[s] = tile_off<D>(r, 2 * s + g);
+  for (int s = 0; s < NS; ++s) koff[s] = lds0 + tile_off<D>(r, 2 * s + g);
   int toff[2][NDB];
 #pragma unroll
   for (int h2 = 0; h2 < 2; ++h2)
 #pragma unroll
     for (int b = 0; b < NDB; ++b)
-      toff[h2][b] = tile_off<D>(4 * g + (li >> 2) + 8 * h2, 4 * b + 2 * dh + ((li >> 1) & 1)) + 8 * (li & 1);
+      toff[h2][b] = lds0 + tile_off<D>(4 * g + (li >> 2) + 8 * h2, 4 * b + 2 * dh + ((li >> 1) & 1)) + 8 * (li & 1);
 
   f32x16 acc[NDB];
 #pragma unroll
@@ -165,41 +169,55 @@ __global__ __launch_bounds__(512, 2) void ca_bwd_dq_kernel(const FwdUnit *__rest
     barrier_nofence();      // ... and everybody else's; everybody is done with tile j-1
     issue_kv(kg, S::K_OFF, j + 3);
     issue_kv(vg, S::V_OFF, j + 3);
-    if (j0 > wmax) continue;  // no row of this wave sees the tile
-    const char *kt = smem + S::K_OFF + (j % NST) * S::TILE;
-    const char *vt = smem + S::V_OFF + (j % NST) * S::TILE;
+    const bool seen = j0 <= wmax;  // some row of this wave sees the tile
+    constexpr int kt = S::K_OFF, vt = S::V_OFF;  // koff / toff address the current stage
     const bool masked = j0 + FWD_BN - 1 > wmin;
+    // one 64-key tile; MASKED is a compile-time constant in each of the two instantiations below
+    auto tile = [&](const bool MASKED) __attribute__((always_inline)) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      f32x16 sa, pa;
+      for (int kb = 0; kb < 2; ++kb) {
+        f32x16 sa, pa;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) sa[i] = 0.f, pa[i] = 0.f;
+        for (int i = 0; i < 16; ++i) sa[i] = 0.f, pa[i] = 0.f;
 #pragma unroll
-      for (int s = 0; s < NS; ++s) {
-        sa = mfma32(lds_read8(kt + koff[s] + 32 * kb * ROWB), qf[s], sa);
-        pa = mfma32(lds_read8(vt + koff[s] + 32 * kb * ROWB), dof[s], pa);
-      }
-      uint32_t dw[8];
-#pragma unroll
-      for (int i = 0; i < 16; i += 2) {
-        float p0 = fast_exp2(fmaf(sa[i], c, -l2)), p1 = fast_exp2(fmaf(sa[i + 1], c, -l2));
-        if (masked) {
-          const int key = j0 + 32 * kb + (i >> 2) * 8 + 4 * g + (i & 3);
-          if (key > pos) p0 = 0.f;
-          if (key + 1 > pos) p1 = 0.f;
+        for (int s = 0; s < NS; ++s) {
+          sa = mfma32(lds_read8_at(kt + koff[s] + 32 * kb * ROWB), qf[s], sa);
+          pa = mfma32(lds_read8_at(vt + koff[s] + 32 * kb * ROWB), dof[s], pa);
         }
-        dw[i >> 1] = pack_bf16(p0 * (pa[i] + dl), p1 * (pa[i + 1] + dl));  // dl holds -Delta
-      }
+        uint32_t dw[8];
+        // register i holds key j0 + 32 kb + 4 g + 8 (i / 4) + i % 4: visible iff 8 (i / 4) + i % 4 <= vis
+        const int vis = pos - (j0 + 32 * kb + 4 * g);
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const bf16x8 db = __builtin_bit_cast(bf16x8, u32x4{dw[4 * t], dw[4 * t + 1], dw[4 * t + 2], dw[4 * t + 3]});
-        const int ro = (32 * kb + 16 * t) * ROWB;
+        for (int i = 0; i < 16; i += 2) {
+          float p0 = fast_exp2(fmaf(sa[i], c, -l2)), p1 = fast_exp2(fmaf(sa[i + 1], c, -l2));
+          if (MASKED) {
+            p0 = (i >> 2) * 8 + (i & 3) <= vis ? p0 : 0.f;
+            p1 = (i >> 2) * 8 + (i & 3) + 1 <= vis ? p1 : 0.f;
+          }
+          dw[i >> 1] = pack_bf16(p0 * (pa[i] + dl), p1 * (pa[i + 1] + dl));  // dl holds -Delta
+        }
 #pragma unroll
-        for (int b = 0; b < NDB; ++b) {
-          const bf16x8 a = join(lds_read_tr4(kt + toff[0][b] + ro), lds_read_tr4(kt + toff[1][b] + ro));
-          acc[b] = mfma32(a, db, acc[b]);
+        for (int t = 0; t < 2; ++t) {
+          const bf16x8 db = __builtin_bit_cast(bf16x8, u32x4{dw[4 * t], dw[4 * t + 1], dw[4 * t + 2], dw[4 * t + 3]});
+          const int ro = (32 * kb + 16 * t) * ROWB;
+#pragma unroll
+          for (int b = 0; b < NDB; ++b) {
+            const bf16x8 a = join(lds_read_tr4_at(kt + toff[0][b] + ro), lds_read_tr4_at(kt + toff[1][b] + ro));
+            acc[b] = mfma32(a, db, acc[b]);
+          }
         }
       }
+    };
+    if (seen) {
+      if (masked) tile(true);
+      else tile(false);
+    }
+    {  // the offsets follow the stages round
+      const int adv = (j % NST) == NST - 1 ? -(NST - 1) * S::STAGE : S::STAGE;
+#pragma unroll
+      for (int s = 0; s < NS; ++s) koff[s] += adv;
+#pragma unroll
+      for (int b = 0; b < NDB; ++b) toff[0][b] += adv, toff[1][b] += adv;
     }
   }
   wait_vmcnt<0>();
