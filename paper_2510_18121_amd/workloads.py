@@ -201,6 +201,38 @@ def larger_model(seed: int = 5, total: int = 262144, hq: int = 64, hkv: int = 8,
     return _mk("cfg5_larger_256k", hq, hkv, 128, lens, list(range(len(lens))), tasks, list(range(len(tasks))), seed)
 
 
+def shard_chunk(shard_len: int, mode: str = "distinct", seed: int = 0, chunk_tokens: int = 32768,
+                max_context: int = 16384, hq: int = 8, hkv: int = 2, d: int = 128) -> Batch:
+    """One chunk of the throughput-versus-shard-length experiment (Section 3.3, "Divisibility and kernel
+    composability": a 32K-token chunk packed of document shards of one fixed length, the context size of each
+    shard drawn at random, several chunks per length).
+
+    mode "distinct": every shard comes from a document of its own; its context (the number of earlier tokens
+    of that document, resident as KV) is a multiple of 16 drawn uniformly from [0, max_context].
+    mode "shared": the chunk's shards are ALL the shards of chunk_tokens / max_context documents of max_context
+    tokens each, in shuffled order - the case the paper's scheduler produces when it cuts a document and sends
+    the pieces to one server.
+    """
+    rng = np.random.default_rng(7000 + 131 * seed + shard_len)
+    n = chunk_tokens // shard_len
+    assert n >= 1 and n * shard_len == chunk_tokens
+    if mode == "distinct":
+        ctx = 16 * rng.integers(0, max_context // 16 + 1, size=n)
+        doc_lens = [int(c) + shard_len for c in ctx]
+        tasks = [(i, int(ctx[i]), shard_len) for i in range(n)]
+    elif mode == "shared":
+        n_docs = max(1, chunk_tokens // max_context)
+        per = chunk_tokens // n_docs
+        assert per % shard_len == 0
+        doc_lens = [per] * n_docs
+        tasks = [(dd, a, shard_len) for dd in range(n_docs) for a in range(0, per, shard_len)]
+    else:
+        raise ValueError(mode)
+    order = rng.permutation(len(tasks)).tolist()
+    return _mk(f"shard_chunk_{mode}_{shard_len}", hq, hkv, d, doc_lens, list(range(len(doc_lens))), tasks, order,
+               seed, {"shard_len": shard_len, "mode": mode})
+
+
 def config(index: int, downscale: int = 1) -> Batch:
     """Workload `index` (1..5); downscale > 1 gives the token-count/downscale twin from the same generator."""
     s = downscale
