@@ -37,3 +37,36 @@ def test_latency_grid_predicts_unmeasured_tasks():
         pred = g.predict(ql, kl)
         print(f"task q={ql} kv={kl}: measured {t * 1e6:.0f} us, predicted {pred * 1e6:.0f} us", flush=True)
         assert 0.4 * t <= pred <= 2.5 * t
+
+
+def test_scheduled_servers_together_equal_the_single_call():
+    """Disaggregation on one GPU: the tasks of a batch are scheduled over 4 virtual servers (Items are cut and
+    moved), every server runs its own fused call on the rows it was given, and the pieces are put back together:
+    O, LSE and dQ row by row, dK and dV summed over the servers.  The result is compared with the oracle on the
+    whole batch (and with the single fused call)."""
+    from paper_2510_18121_amd import scheduler as S
+
+    b = W.one_kv_group(W.config(3, 16))
+    q, k, v, d_o = W.make_tensors(b, DEV)
+    whole = P.run_hip(b, q, k, v, d_o)
+    ref = P.run_oracle(b, q, k, v, d_o)
+    items = S.items_from_batch(b, 4)
+    sch = S.schedule(items, 4, size_q=1024.0, size_kv=512.0, eps=0.02)
+    assert sch.moves and sch.imbalance() <= 1.03
+    o, dq = torch.zeros_like(q), torch.zeros_like(q)
+    lse = torch.zeros_like(whole["lse"])
+    dk, dv = torch.zeros(k.shape, device=DEV), torch.zeros(v.shape, device=DEV)  # fp32 sums over servers
+    for srv in sch.servers:
+        sub, qrows, kvrows = S.server_batch(b, srv)
+        qi, ki = torch.as_tensor(qrows, device=DEV), torch.as_tensor(kvrows, device=DEV)
+        h = P.run_hip(sub, q[qi].contiguous(), k[ki].contiguous(), v[ki].contiguous(), d_o[qi].contiguous())
+        o[qi], dq[qi] = h["o"], h["dq"]
+        lse[:, qi] = h["lse"]
+        dk.index_add_(0, ki, h["dk"].float())
+        dv.index_add_(0, ki, h["dv"].float())
+    e = P.errors({"o": o, "lse": lse, "dq": dq, "dk": dk, "dv": dv}, ref)
+    print("4 servers put together:", e, flush=True)
+    P.assert_parity(e, "scheduled servers")
+    # against the single fused call: same rows, at most one bf16 unit apart where tiles were cut differently
+    assert (o.float() - whole["o"].float()).abs().max().item() <= 2.0 ** -5
+    assert (lse - whole["lse"]).abs().max().item() <= 1e-5
