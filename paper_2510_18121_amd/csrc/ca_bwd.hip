@@ -25,11 +25,13 @@ namespace ca {
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float L2_PADDING = 1.0e30f;  // exp2(x - 1e30) == 0 for every finite score
 
-__global__ void ca_bwd_prep_kernel(const int32_t *__restrict__ slot_row, const bf16_t *__restrict__ O,
-                                   const bf16_t *__restrict__ dO, const float *__restrict__ LSE,
-                                   float *__restrict__ delta_slot, float *__restrict__ l2_slot, int64_t padded,
-                                   int64_t total_q, int Hq, int D) {
-  // D/8 lanes per (slot, head)
+__global__ void ca_bwd_prep_kernel(const int32_t *__restrict__ slot_row, const bf16_t *__restrict__ Q,
+                                   const bf16_t *__restrict__ O, const bf16_t *__restrict__ dO,
+                                   const float *__restrict__ LSE, float *__restrict__ delta_slot,
+                                   float *__restrict__ l2_slot, bf16_t *__restrict__ q_sorted,
+                                   bf16_t *__restrict__ do_sorted, int64_t padded, int64_t total_q, int Hq, int D) {
+  // D/8 lanes per (slot, head): -Delta = -<dO, O> and log2(e)*LSE in slot order, and the slot-ordered copies of
+  // Q and dO, [head][slot][D] (padding slots: zeros, with an LSE that makes every probability 0)
   const int lanes = D / 8;
   const int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
   const int64_t pair = idx / lanes;
@@ -39,17 +41,25 @@ __global__ void ca_bwd_prep_kernel(const int32_t *__restrict__ slot_row, const b
   const int h = int(pair % Hq);
   const int row = ok ? slot_row[slot] : -1;
   float s = 0.f;
+  u32x4 qv = {0, 0, 0, 0}, dv = {0, 0, 0, 0};
   if (row >= 0) {
     const size_t off = (size_t(row) * Hq + h) * D + 8 * c;
     const bf16x8 a = *reinterpret_cast<const bf16x8 *>(O + off);
     const bf16x8 b = *reinterpret_cast<const bf16x8 *>(dO + off);
+    qv = *reinterpret_cast<const u32x4 *>(Q + off);
+    dv = __builtin_bit_cast(u32x4, b);
 #pragma unroll
     for (int i = 0; i < 8; ++i) s += float(a[i]) * float(b[i]);
   }
   for (int o = lanes / 2; o > 0; o >>= 1) s += __shfl_xor(s, o);
-  if (ok && c == 0) {
-    delta_slot[int64_t(h) * padded + slot] = row >= 0 ? -s : 0.f;  // stored negated: both kernels add it
-    l2_slot[int64_t(h) * padded + slot] = row >= 0 ? LSE[int64_t(h) * total_q + row] * LOG2E : L2_PADDING;
+  if (ok) {
+    const size_t so = (size_t(h) * padded + slot) * D + 8 * c;
+    *reinterpret_cast<u32x4 *>(q_sorted + so) = qv;
+    *reinterpret_cast<u32x4 *>(do_sorted + so) = dv;
+    if (c == 0) {
+      delta_slot[int64_t(h) * padded + slot] = row >= 0 ? -s : 0.f;  // stored negated: both kernels add it
+      l2_slot[int64_t(h) * padded + slot] = row >= 0 ? LSE[int64_t(h) * total_q + row] * LOG2E : L2_PADDING;
+    }
   }
 }
 
@@ -252,10 +262,9 @@ struct DkvSmem {
 
 template <int D>
 __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__restrict__ units,
-                                                            const int32_t *__restrict__ slot_row,
                                                             const int32_t *__restrict__ slot_pos,
-                                                            const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
-                                                            const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
+                                                            const bf16_t *__restrict__ Qs, const bf16_t *__restrict__ K,
+                                                            const bf16_t *__restrict__ V, const bf16_t *__restrict__ dOs,
                                                             const float *__restrict__ l2_slot,
                                                             const float *__restrict__ delta_slot,
                                                             bf16_t *__restrict__ dK, bf16_t *__restrict__ dV, int Hq,
@@ -285,46 +294,33 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   const int n_fast = ((u.slot_end - u.slot_full) / BWD_BQ) * G;
 
   // ---- loads of one (q block, head): this wave fetches tile rows RPW*wave .. +RPW-1 of Q and of dO, plus one
-  // 64-float auxiliary array.
+  // 64-float auxiliary array.  Q and dO come from their slot-ordered copies [head][slot][D], in which the tile of a
+  // (block, head) is one contiguous run: a load is (wave-uniform tile address) + (per-lane constant).
   const int ld_rr = lane / CH;  // row inside one direct load
-  int ld_coff[NLD];             // element offset of the lane's chunk in its global row
+  uint32_t ld_off[NLD];         // byte offset of the lane's chunk from the start of the tile
 #pragma unroll
-  for (int n = 0; n < NLD; ++n) ld_coff[n] = 8 * ((lane % CH) ^ tile_sw<D>(RPW * wave + RPI * n + ld_rr));
+  for (int n = 0; n < NLD; ++n) {
+    const int trow = RPW * wave + RPI * n + ld_rr;
+    ld_off[n] = uint32_t(trow * ROWB + 16 * ((lane % CH) ^ tile_sw<D>(trow)));
+  }
   // Prefetch cursor: (pblk, ph) is the next (query block, head of the group) to fetch.  Query blocks are walked
   // from the document's LAST block backwards: every KV tile of a document then starts at the same block, so the
-  // workgroups that run side by side on an XCD (same KV head, neighbouring KV tiles) fetch the same Q/dO rows
-  // at about the same time and share them in that XCD's L2.
-  // The G heads of a block use the same rows, so the per-lane row offsets are computed once per block, from
-  // row indices that were fetched with scalar loads (they do not enter the vector-memory counter that paces
-  // the direct loads) while the previous block was being issued.  Past the last block the cursor stays on it:
-  // every iteration issues the same number of loads, which keeps the s_waitcnt bookkeeping constant.
+  // workgroups that run side by side on an XCD (same KV head, neighbouring KV tiles) fetch the same Q/dO tiles
+  // at about the same time and share them in that XCD's L2.  Past the last block the cursor stays on it: every
+  // iteration issues the same number of loads, which keeps the s_waitcnt bookkeeping constant.
   int pblk = n_blocks - 1, ph = 0, pst = 0;
   uint32_t pst_addr = lds0;  // LDS address of the stage being filled
-  const char *q_head = reinterpret_cast<const char *>(Q), *do_head = reinterpret_cast<const char *>(dO);  // + head ph
-  int rown[RPW];
-  uint64_t rowoff[NLD];
-  const uint32_t row_bytes = uint32_t(Hq) * D * 2;
-  auto load_rows = [&](int blk) __attribute__((always_inline)) {
-    const int32_t CA_CONST *rows = (const int32_t CA_CONST *)(slot_row + u.slot_begin + blk * BWD_BQ + RPW * wave);
-#pragma unroll
-    for (int x = 0; x < RPW; ++x) {
-      rown[x] = rows[x];
-      asm volatile("" : "+s"(rown[x]));  // keep it a scalar: no per-lane gather in place of the selects below
-    }
-  };
-  int ld_sel[RPI];  // all-ones in the lanes whose row inside a direct load is x
-#pragma unroll
-  for (int x = 0; x < RPI; ++x) ld_sel[x] = ld_rr == x ? -1 : 0;
-  auto make_rowoff = [&]() __attribute__((always_inline)) {
-#pragma unroll
-    for (int n = 0; n < NLD; ++n) {
-      int row = 0;  // branch-free select of this lane's row index out of the RPI scalars of load n
-#pragma unroll
-      for (int x = 0; x < RPI; ++x) row |= ld_sel[x] & rown[RPI * n + x];
-      // padding slots read any valid row: their probabilities are 0
-      rowoff[n] = uint64_t(uint32_t(max(row, 0))) * row_bytes + uint32_t((hk * G * D + ld_coff[n]) * 2);
-    }
-  };
+  const int64_t head_stride = padded * D * 2;  // bytes between the tiles of consecutive heads
+  const int64_t tile0 = (int64_t(hk) * G * padded + u.slot_begin + int64_t(pblk) * BWD_BQ) * D * 2;
+  const char *q_tile = reinterpret_cast<const char *>(Qs) + tile0, *do_tile = reinterpret_cast<const char *>(dOs) + tile0;
+  // the wave's auxiliary array: log2e*LSE (wave 0), -Delta (wave 1), slot positions (wave 2; wave 3 repeats them
+  // into a spare area so that every wave issues the same number of loads)
+  const int64_t aux_hstride = wave < 2 ? padded : 0;
+  const float *aux_ptr = (wave == 0 ? l2_slot + int64_t(hk) * G * padded
+                          : wave == 1 ? delta_slot + int64_t(hk) * G * padded
+                                      : reinterpret_cast<const float *>(slot_pos)) +
+                         u.slot_begin + int64_t(pblk) * BWD_BQ + lane;
+  const uint32_t aux_lds = wave == 0 ? S::L2_OFF : wave == 1 ? S::DL_OFF : wave == 2 ? S::POS_OFF : S::SPARE_OFF;
   constexpr int LPI = 2 * NLD + 1;  // loads per wave per iteration
   // The loads of one (block, head) come in LPI pieces, so that the pipelined path can hand them to the memory
   // pipeline a few at a time between its MFMAs (a burst of LPI loads from all four waves at once stalls the
@@ -332,44 +328,36 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   auto issue_piece = [&](int i) __attribute__((always_inline)) {
     if (i < 2 * NLD) {
       const int n = i >> 1;
-      load_lds16_at(((i & 1) ? do_head : q_head) + rowoff[n], pst_addr + ((i & 1) ? S::DO_OFF : S::Q_OFF) + (RPW * wave + RPI * n) * ROWB);
+      load_lds16_sbase((i & 1) ? do_tile : q_tile, ld_off[n],
+                       pst_addr + ((i & 1) ? S::DO_OFF : S::Q_OFF) + (RPW * wave + RPI * n) * ROWB);
       return;
     }
-    const int s0 = u.slot_begin + pblk * BWD_BQ, h = hk * G + ph;
-    const float *aux = wave == 0 ? l2_slot + int64_t(h) * padded + s0
-                     : wave == 1 ? delta_slot + int64_t(h) * padded + s0
-                                 : reinterpret_cast<const float *>(slot_pos) + s0;
-    load_lds4_at(aux + lane, pst_addr + (wave == 0 ? S::L2_OFF : wave == 1 ? S::DL_OFF : wave == 2 ? S::POS_OFF : S::SPARE_OFF));
+    load_lds4_at(aux_ptr, pst_addr + aux_lds);
     pst = pst + 1 == NST ? 0 : pst + 1;
     pst_addr = pst == 0 ? lds0 : pst_addr + S::STAGE;
-    q_head += D * 2, do_head += D * 2;
-    if (++ph == G) {
-      if (pblk > 0) {
-        ph = 0;
-        q_head -= G * D * 2, do_head -= G * D * 2;
-        --pblk;
-        make_rowoff();                      // from the indices fetched G iterations ago
-        if (pblk > 0) load_rows(pblk - 1);  // for the block after this one
-      } else {
-        ph = G - 1;  // past the end: keep re-fetching the final (block, head)
-        q_head -= D * 2, do_head -= D * 2;
-      }
-    }
+    if (ph + 1 < G) {  // next head of the group, same block
+      ++ph;
+      q_tile += head_stride, do_tile += head_stride, aux_ptr += aux_hstride;
+    } else if (pblk > 0) {  // first head of the group, previous block
+      ph = 0;
+      --pblk;
+      q_tile -= (G - 1) * head_stride + BWD_BQ * D * 2, do_tile -= (G - 1) * head_stride + BWD_BQ * D * 2;
+      aux_ptr -= (G - 1) * aux_hstride + BWD_BQ;
+    }  // else: past the end, keep re-fetching the final (block, head)
   };
   auto issue_next = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < LPI; ++i) issue_piece(i);
   };
-  // plain load pieces handed out per phase of the pipelined path after its barrier: second half of B(2 it + 1),
-  // A(2 it + 2), B(2 it + 2), A(2 it + 3); the cursor piece follows the last one
-  constexpr int NB1 = D == 128 ? 2 : 1, NA0 = D == 128 ? 3 : 1, NB0 = D == 128 ? 3 : 1;
-  constexpr int NA1 = LPI - 1 - NB1 - NA0 - NB0;
+  // Load pieces of the pipelined path go out during its gradient phases (few other instructions there): after the
+  // barrier in the second half of B(2 it + 1) pieces 0 .. NB1-1 at MFMA slots PB1 .., and in B(2 it + 2) the other
+  // NB0 pieces (the cursor piece last) at slots PB0 ..
+  constexpr int NB1 = D == 128 ? 5 : 3, PB1 = D == 128 ? 10 : 5;
+  constexpr int NB0 = LPI - NB1, PB0 = D == 128 ? 4 : 2;
+  static_assert(NB1 < LPI && PB1 + NB1 <= 4 * NDB && PB1 >= 2 * NDB && PB0 + NB0 <= 4 * NDB, "piece schedule");
   constexpr int LP1 = NB1;  // pieces of the newest block that are issued before the pipelined path takes over
 
   if (n_it > 0) {
-    load_rows(pblk);
-    make_rowoff();
-    if (pblk > 0) load_rows(pblk - 1);
     issue_next();  // blocks 0 .. 3: four ahead; the last one is completed further down
     issue_next();
     issue_next();
@@ -452,7 +440,6 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
     auxo += adv;
   };
   constexpr int SUB = 32 * ROWB, HALF = 16 * ROWB;
-  static_assert(NA1 >= 0 && NA1 <= NS / 2 && NA0 <= NS / 2 && NB0 <= 4 && NB1 <= 2, "piece schedule");
   int it = 0;
   if (n_fast > 0) {
     f32x16 sc[2], dp[2];  // score tiles S and dP - Delta of sub-blocks k (even: [0], odd: [1])
@@ -472,21 +459,31 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
         for (int e = 0; e < 4; ++e) ndt[4 * i4 + e] = x[e];
       }
     };
-    // P of query rows 4 i4 + 2 h, + 1 of this lane's 16 (h = 0, 1): half a group of four
+    // P of query rows 4 i4 + 2 h, + 1 of this lane's 16 (h = 0, 1): half a group of four.
+    // The empty volatile asm on one input of each piece of vector work keeps the instruction selector from hoisting
+    // the (side-effect-free) arithmetic across the sched_barrier fences of earlier MFMA slots: the work of a slot
+    // stays in its slot.
     auto vec_p = [&](const f32x16 &sa, int i4, int h) __attribute__((always_inline)) {
+      {
+        float g = l2v[i4][2 * h];
+        pin(g);
+        l2v[i4][2 * h] = g;
+      }
 #pragma unroll
       for (int e = 2 * h; e < 2 * h + 2; ++e) pv[4 * i4 + e] = fast_exp2(fmaf(sa[4 * i4 + e], c, -l2v[i4][e]));
       pw[2 * i4 + h] = pack_bf16(pv[4 * i4 + 2 * h], pv[4 * i4 + 2 * h + 1]);
     };
     auto vec_ds = [&](const f32x16 &da, int i4) __attribute__((always_inline)) {
+      pin(pv[4 * i4]);
       dw[2 * i4] = pack_bf16(pv[4 * i4] * da[4 * i4], pv[4 * i4 + 1] * da[4 * i4 + 1]);
       dw[2 * i4 + 1] = pack_bf16(pv[4 * i4 + 2] * da[4 * i4 + 2], pv[4 * i4 + 3] * da[4 * i4 + 3]);
     };
     // Score chain of one sub-block into (sw, dpw); nat = offset of its natural tiles from qoff's stage.  With VEC,
-    // P of (sr) is formed between the MFMAs, and the transposed first-half fragments of the sub-block at offset
-    // `tro` of toff's stage are fetched.  Load pieces piece0 .. piece0 + np - 1 go out at the odd steps.
-    auto phase_a = [&](f32x16 &sw, f32x16 &dpw, const f32x16 &sr, int nat, int tro, bool vec, int piece0, int np,
-                       bool cursor_piece) __attribute__((always_inline)) {
+    // P of the first 12 of the lane's 16 rows of (sr) is formed between the MFMAs (the rest follows in phase B: the
+    // vector ALU's share of a phase must fit under its MFMAs), and the transposed first-half fragments of the
+    // sub-block at offset `tro` of toff's stage are fetched.
+    auto phase_a = [&](f32x16 &sw, f32x16 &dpw, const f32x16 &sr, int nat, int tro, bool vec)
+                       __attribute__((always_inline)) {
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
         // every MFMA is followed by its share of the other work, so that the next one finds the matrix pipe free
@@ -496,9 +493,9 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
           const int X = ((s & 1) ? S::Q_OFF : S::DO_OFF) + tro;
           opb[s] = join(lds_read_tr4_at(X + toff[0][s >> 1]), lds_read_tr4_at(X + toff[1][s >> 1]));
           if constexpr (NS == 8) {
-            vec_p(sr, s >> 1, s & 1);
+            if (s < 6) vec_p(sr, s >> 1, s & 1);
           } else {
-            vec_p(sr, s, 0);
+            if (s < 3) vec_p(sr, s, 0);
           }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -509,14 +506,14 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
           opd[s % PA] = lds_read8_at(S::DO_OFF + nat + qoff[s + PA]);
           opq[s % PA] = lds_read8_at(S::Q_OFF + nat + qoff[s + PA]);
         }
-        if ((s & 1) && (s >> 1) < np) issue_piece(piece0 + (s >> 1));
         if (vec) {
-          if constexpr (NS != 8) vec_p(sr, s, 1);
+          if constexpr (NS != 8) {
+            if (s < 3) vec_p(sr, s, 1);
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
       }
       mfma_settle(sw, dpw, ndt);
-      if (cursor_piece) issue_piece(LPI - 1);  // the piece with the cursor's branches stays outside the chain
     };
 
     // blocks 0 and 1 have landed (this wave's part); block 2 and the issued part of block 3 may be in flight
@@ -528,7 +525,7 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
       opq[s] = lds_read8_at(S::Q_OFF + qoff[s]);
     }
     load_nd(auxq);
-    phase_a(sc[0], dp[0], sc[0], 0, 0, false, 0, 0, false);
+    phase_a(sc[0], dp[0], sc[0], 0, 0, false);
 #pragma unroll
     for (int s = 0; s < PA; ++s) {
       opd[s] = lds_read8_at(S::DO_OFF + SUB + qoff[s]);
@@ -542,8 +539,8 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
       for (int qb = 0; qb < 2; ++qb) {
         // ---- phase A: scores of the next sub-block (the other half of this block, or the first half of the
         // next block), P of this one
-        if (qb == 0) phase_a(sc[1], dp[1], sc[0], SUB, 0, true, NB1, NA0, false);
-        else phase_a(sc[0], dp[0], sc[1], 0, SUB, true, NB1 + NA0 + NB0, NA1, true);
+        if (qb == 0) phase_a(sc[1], dp[1], sc[0], SUB, 0, true);
+        else phase_a(sc[0], dp[0], sc[1], 0, SUB, true);
         if (qb == 0) advance_q();  // natural reads and chain statistics now address block it+1
         // ---- phase B
         const int QT = S::Q_OFF + qb * SUB, DOT = S::DO_OFF + qb * SUB;  // this sub-block's tiles inside the stage
@@ -575,10 +572,19 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
                 if (t == 0)
                   opb[2 * b + 1] = join(lds_read_tr4_at(QT + HALF + toff[0][b]), lds_read_tr4_at(QT + HALF + toff[1][b]));
               }
-              // dS of this sub-block, during the first dV group
-              if (t == 0 && w == 0) {
-#pragma unroll
-                for (int i4 = (4 * b) / NDB; i4 < (4 * (b + 1)) / NDB; ++i4) vec_ds(dp[qb], i4);
+              // the vector ALU's share of this phase: dS of rows 0..7 before the first dK group, the last quarter
+              // of P before the second dV group, dS of rows 8..15 before the second dK group
+              if constexpr (NDB == 4) {
+                if (m == 0) vec_ds(dp[qb], 0);
+                if (m == 1) vec_ds(dp[qb], 1);
+                if (m == 2) vec_p(sc[qb], 3, 0);
+                if (m == 3) vec_p(sc[qb], 3, 1);
+                if (m == 8) vec_ds(dp[qb], 2);
+                if (m == 9) vec_ds(dp[qb], 3);
+              } else {
+                if (m == 0) vec_ds(dp[qb], 0), vec_ds(dp[qb], 1);
+                if (m == 1) vec_p(sc[qb], 3, 0), vec_p(sc[qb], 3, 1);
+                if (m == 4) vec_ds(dp[qb], 2), vec_ds(dp[qb], 3);
               }
               // first natural fragments of sub-block k+2 (block it+1: first half for qb == 0, second for qb == 1)
 #pragma unroll
@@ -587,13 +593,10 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
                 if (o & 1) opq[sn] = lds_read8_at(S::Q_OFF + qb * SUB + qoff[sn]);
                 else opd[sn] = lds_read8_at(S::DO_OFF + qb * SUB + qoff[sn]);
               }
-              // load pieces: the block that the barrier has just made room for (qb == 1), and more of it one
-              // phase later (qb == 0)
-              if (b == NDB - 1) {
-                const int grp = 2 * t + w;
-                if (qb == 1 && t == 1 && w < NB1) issue_piece(w);
-                if (qb == 0 && grp < NB0) issue_piece(NB1 + NA0 + grp);
-              }
+              // load pieces: the block that the barrier has just made room for (qb == 1), the rest of it one
+              // phase B later (qb == 0)
+              if (qb == 1 && m >= PB1 && m < PB1 + NB1) issue_piece(m - PB1);
+              if (qb == 0 && m >= PB0 && m < PB0 + NB0) issue_piece(NB1 + m - PB0);
               __builtin_amdgcn_sched_barrier(0);
             }
           }
@@ -722,6 +725,8 @@ static hipError_t launch_bwd_t(const ca_plan_t *p, const void *q, const void *k,
   const int64_t padded = int64_t(p->slot_row.size());
   float *delta_slot = static_cast<float *>(ws);
   float *l2_slot = reinterpret_cast<float *>(static_cast<char *>(ws) + p->ws_off_l2);
+  bf16_t *q_sorted = reinterpret_cast<bf16_t *>(static_cast<char *>(ws) + p->ws_off_qs);
+  bf16_t *do_sorted = reinterpret_cast<bf16_t *>(static_cast<char *>(ws) + p->ws_off_dos);
   // rows that belong to no work unit (KV outside every scheduled document, Q rows outside every task)
   if (!p->kv_covered) {
     launch_fill(dk, kv_elems * 2, st);
@@ -731,8 +736,8 @@ static hipError_t launch_bwd_t(const ca_plan_t *p, const void *q, const void *k,
   if (padded > 0) {
     const int64_t threads = padded * p->hq * (D / 8);
     hipLaunchKernelGGL(ca_bwd_prep_kernel, dim3(unsigned((threads + 255) / 256)), dim3(256), 0, st, p->d_slot_row,
-                       static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(d_o), lse, delta_slot, l2_slot,
-                       padded, p->total_q, p->hq, D);
+                       static_cast<const bf16_t *>(q), static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(d_o),
+                       lse, delta_slot, l2_slot, q_sorted, do_sorted, padded, p->total_q, p->hq, D);
   }
   if (ev) (void)hipEventRecord(ev[1], st);
   if (!p->bwd_units.empty()) {
@@ -741,8 +746,8 @@ static hipError_t launch_bwd_t(const ca_plan_t *p, const void *q, const void *k,
     hipError_t e = set_smem(kern, DkvSmem<D>::TOTAL, p->device, done);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(unsigned(p->bwd_units.size())), dim3(256), DkvSmem<D>::TOTAL, st, p->d_bwd_units,
-                       p->d_slot_row, p->d_slot_pos, static_cast<const bf16_t *>(q), static_cast<const bf16_t *>(k),
-                       static_cast<const bf16_t *>(v), static_cast<const bf16_t *>(d_o), l2_slot, delta_slot,
+                       p->d_slot_pos, q_sorted, static_cast<const bf16_t *>(k), static_cast<const bf16_t *>(v),
+                       do_sorted, l2_slot, delta_slot,
                        static_cast<bf16_t *>(dk), static_cast<bf16_t *>(dv), p->hq, p->hkv, padded, p->scale);
   }
   if (ev) (void)hipEventRecord(ev[2], st);

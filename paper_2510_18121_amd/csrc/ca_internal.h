@@ -49,7 +49,7 @@ struct ca_plan {
   std::vector<ca::BwdUnit> bwd_units;
   int64_t fwd_steps = 0, bwd_steps = 0;
   // workspace layout for backward: [Delta fp32 hq*padded_slots][log2e*LSE fp32 hq*padded_slots]
-  size_t ws_fwd = 0, ws_bwd = 0, ws_off_l2 = 0;
+  size_t ws_fwd = 0, ws_bwd = 0, ws_off_l2 = 0, ws_off_qs = 0, ws_off_dos = 0;
   bool q_covered = false, kv_covered = false;  // every packed Q row / KV row belongs to some unit
   // device copies
   int device = -1;
