@@ -274,7 +274,7 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   constexpr int NLD = BWD_BQ / (4 * RPI);  // direct loads per wave per Q (or dO) tile
   constexpr int RPW = BWD_BQ / 4;          // tile rows fetched by one wave (contiguous)
   constexpr int ROWB = 2 * D;
-  constexpr int PA = NS < 4 ? NS : 4;      // k-steps of natural Q/dO fragments held ahead of their MFMAs
+  constexpr int PA = NS;                   // k-steps of natural Q/dO fragments held ahead of their MFMAs (all)
   constexpr int PFB = (2 * PA) / (2 * NDB);  // natural fragments fetched per gradient MFMA pair
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
@@ -349,12 +349,21 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
 #pragma unroll
     for (int i = 0; i < LPI; ++i) issue_piece(i);
   };
-  // Load pieces of the pipelined path go out during its gradient phases (few other instructions there): after the
-  // barrier in the second half of B(2 it + 1) pieces 0 .. NB1-1 at MFMA slots PB1 .., and in B(2 it + 2) the other
-  // NB0 pieces (the cursor piece last) at slots PB0 ..
-  constexpr int NB1 = D == 128 ? 5 : 3, PB1 = D == 128 ? 10 : 5;
-  constexpr int NB0 = LPI - NB1, PB0 = D == 128 ? 4 : 2;
-  static_assert(NB1 < LPI && PB1 + NB1 <= 4 * NDB && PB1 >= 2 * NDB && PB0 + NB0 <= 4 * NDB, "piece schedule");
+  // Load pieces of the pipelined path go out during its gradient phases (few other instructions there), spread so
+  // that the four waves' pieces do not pile up in the memory pipeline (one 1 KB load per 16 cycles per CU): by MFMA
+  // slot of the phase, after the barrier in B(2 it + 1), then in B(2 it + 2), then in B(2 it + 3) before its
+  // barrier (the cursor piece last).  slot -> piece index, or -1.
+  constexpr int NPOST = D == 128 ? 2 : 1, NMID = D == 128 ? 5 : 3, NPRE = LPI - NPOST - NMID;
+  static_assert(NPRE >= 1 && NPRE <= 2, "piece schedule");
+  auto piece_of = [](int qb, int m) constexpr -> int {
+    if (D == 128) {
+      if (qb == 1) return m == 10 ? 0 : m == 13 ? 1 : m == 4 ? NPOST + NMID : m == 6 ? NPOST + NMID + 1 : -1;
+      return m == 4 ? NPOST : m == 6 ? NPOST + 1 : m == 10 ? NPOST + 2 : m == 12 ? NPOST + 3 : m == 14 ? NPOST + 4 : -1;
+    }
+    if (qb == 1) return m == 6 ? 0 : m == 2 ? NPOST + NMID : -1;
+    return m == 2 ? NPOST : m == 3 ? NPOST + 1 : m == 6 ? NPOST + 2 : -1;
+  };
+  constexpr int NB1 = NPOST;
   constexpr int LP1 = NB1;  // pieces of the newest block that are issued before the pipelined path takes over
 
   if (n_it > 0) {
@@ -459,19 +468,19 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
         for (int e = 0; e < 4; ++e) ndt[4 * i4 + e] = x[e];
       }
     };
-    // P of query rows 4 i4 + 2 h, + 1 of this lane's 16 (h = 0, 1): half a group of four.
+    // P of query row 4 i4 + e of this lane's 16 (e = 0..3), and after every second one the packed pair.
     // The empty volatile asm on one input of each piece of vector work keeps the instruction selector from hoisting
     // the (side-effect-free) arithmetic across the sched_barrier fences of earlier MFMA slots: the work of a slot
     // stays in its slot.
+    auto vec_p1 = [&](const f32x16 &sa, int i4, int e) __attribute__((always_inline)) {
+      float g = l2v[i4][e];
+      pin(g);
+      pv[4 * i4 + e] = fast_exp2(fmaf(sa[4 * i4 + e], c, -g));
+      if (e & 1) pw[2 * i4 + (e >> 1)] = pack_bf16(pv[4 * i4 + e - 1], pv[4 * i4 + e]);
+    };
     auto vec_p = [&](const f32x16 &sa, int i4, int h) __attribute__((always_inline)) {
-      {
-        float g = l2v[i4][2 * h];
-        pin(g);
-        l2v[i4][2 * h] = g;
-      }
-#pragma unroll
-      for (int e = 2 * h; e < 2 * h + 2; ++e) pv[4 * i4 + e] = fast_exp2(fmaf(sa[4 * i4 + e], c, -l2v[i4][e]));
-      pw[2 * i4 + h] = pack_bf16(pv[4 * i4 + 2 * h], pv[4 * i4 + 2 * h + 1]);
+      vec_p1(sa, i4, 2 * h);
+      vec_p1(sa, i4, 2 * h + 1);
     };
     auto vec_ds = [&](const f32x16 &da, int i4) __attribute__((always_inline)) {
       pin(pv[4 * i4]);
@@ -486,14 +495,17 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
                        __attribute__((always_inline)) {
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
-        // every MFMA is followed by its share of the other work, so that the next one finds the matrix pipe free
+        // every MFMA is followed by its share of the other work (one transposed fragment half, one exponential),
+        // so that the next one finds the matrix pipe free
+        const int X = ((s & 1) ? S::Q_OFF : S::DO_OFF) + tro;
+        bf16x4 tlo, thi;
         if (s == 0) mfma32_v_first(sw, opq[0], kf[0]);
         else mfma32_v(sw, opq[s % PA], kf[s]);
+        if (s + PA < NS) opq[s % PA] = lds_read8_at(S::Q_OFF + nat + qoff[s + PA]);
         if (vec) {
-          const int X = ((s & 1) ? S::Q_OFF : S::DO_OFF) + tro;
-          opb[s] = join(lds_read_tr4_at(X + toff[0][s >> 1]), lds_read_tr4_at(X + toff[1][s >> 1]));
+          tlo = lds_read_tr4_at(X + toff[0][s >> 1]);
           if constexpr (NS == 8) {
-            if (s < 6) vec_p(sr, s >> 1, s & 1);
+            if (s < 6) vec_p1(sr, s >> 1, 2 * (s & 1));
           } else {
             if (s < 3) vec_p(sr, s, 0);
           }
@@ -501,13 +513,13 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
         __builtin_amdgcn_sched_barrier(0);
         if (s == 0) mfma32_v_first(dpw, opd[0], vf[0], ndt);
         else mfma32_v(dpw, opd[s % PA], vf[s]);
-        if (s + PA < NS) {
-          // dO before Q: the S MFMA that comes first waits for the younger of the two reads, which covers both
-          opd[s % PA] = lds_read8_at(S::DO_OFF + nat + qoff[s + PA]);
-          opq[s % PA] = lds_read8_at(S::Q_OFF + nat + qoff[s + PA]);
-        }
+        if (s + PA < NS) opd[s % PA] = lds_read8_at(S::DO_OFF + nat + qoff[s + PA]);
         if (vec) {
-          if constexpr (NS != 8) {
+          thi = lds_read_tr4_at(X + toff[1][s >> 1]);
+          opb[s] = join(tlo, thi);
+          if constexpr (NS == 8) {
+            if (s < 6) vec_p1(sr, s >> 1, 2 * (s & 1) + 1);
+          } else {
             if (s < 3) vec_p(sr, s, 1);
           }
         }
@@ -595,8 +607,7 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
               }
               // load pieces: the block that the barrier has just made room for (qb == 1), the rest of it one
               // phase B later (qb == 0)
-              if (qb == 1 && m >= PB1 && m < PB1 + NB1) issue_piece(m - PB1);
-              if (qb == 0 && m >= PB0 && m < PB0 + NB0) issue_piece(NB1 + m - PB0);
+              if (piece_of(qb, m) >= 0) issue_piece(piece_of(qb, m));
               __builtin_amdgcn_sched_barrier(0);
             }
           }
