@@ -172,6 +172,18 @@ __global__ __launch_bounds__(512, 2) void ca_bwd_dq_kernel(const FwdUnit *__rest
 #pragma unroll
   for (int s = 0; s < NS; ++s) pin(qf[s]), pin(dof[s]);
   pin(l2), pin(dl);
+  // -Delta enters dP through the matrix pipe: one more k-step whose A fragment is 1 in two k-slots of every key row
+  // and whose B fragment holds -Delta of the lane's query row split in two bf16 (hi + lo, 16 bits of mantissa) in
+  // the same two slots.  One MFMA per 32 keys instead of 16 vector additions: this kernel is bound by its vector
+  // ALU work (the exponentials run at quarter rate), not by the matrix pipe.
+  bf16x8 ones_f, dl_f;
+  {
+    const bf16_t hi = bf16_t(dl), lo = bf16_t(dl - float(hi));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ones_f[i] = bf16_t(0.f), dl_f[i] = bf16_t(0.f);
+    if (g == 0) ones_f[0] = bf16_t(1.f), ones_f[1] = bf16_t(1.f), dl_f[0] = hi, dl_f[1] = lo;
+  }
+  pin(ones_f), pin(dl_f);
 
   for (int j = 0; j < n_tiles; ++j) {
     const int j0 = j * FWD_BN;
@@ -194,6 +206,7 @@ __global__ __launch_bounds__(512, 2) void ca_bwd_dq_kernel(const FwdUnit *__rest
           sa = mfma32(lds_read8_at(kt + koff[s] + 32 * kb * ROWB), qf[s], sa);
           pa = mfma32(lds_read8_at(vt + koff[s] + 32 * kb * ROWB), dof[s], pa);
         }
+        pa = mfma32(ones_f, dl_f, pa);  // dP - Delta
         uint32_t dw[8];
         // register i holds key j0 + 32 kb + 4 g + 8 (i / 4) + i % 4: visible iff 8 (i / 4) + i % 4 <= vis
         const int vis = pos - (j0 + 32 * kb + 4 * g);
@@ -204,7 +217,7 @@ __global__ __launch_bounds__(512, 2) void ca_bwd_dq_kernel(const FwdUnit *__rest
             p0 = (i >> 2) * 8 + (i & 3) <= vis ? p0 : 0.f;
             p1 = (i >> 2) * 8 + (i & 3) + 1 <= vis ? p1 : 0.f;
           }
-          dw[i >> 1] = pack_bf16(p0 * (pa[i] + dl), p1 * (pa[i + 1] + dl));  // dl holds -Delta
+          dw[i >> 1] = pack_bf16(p0 * pa[i], p1 * pa[i + 1]);
         }
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
