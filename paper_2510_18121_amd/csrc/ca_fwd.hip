@@ -51,6 +51,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   constexpr int ROWB = 2 * D;
   constexpr float RESCALE_LOG2 = 8.0f;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(CA_LDS char *)smem;  // LDS byte address of the dynamic segment
 
   const FwdUnit u = units[blockIdx.x];
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, r = lane & 31;
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   auto issue_kv = [&](const char *src, int area, int tile) __attribute__((always_inline)) {
     const bool last = tile >= last_tile;
     const char *base = src + size_t(last ? last_tile : tile) * tile_bytes;
-    const uint32_t dst = uint32_t(area + (tile % NST) * S::TILE + 1024 * wave);
+    const uint32_t dst = lds0 + uint32_t(area + (tile % NST) * S::TILE + 1024 * wave);
 #pragma unroll
     for (int n = 0; n < NLD; ++n) load_lds16_sbase(base, last ? ld_off_last[n] : ld_off[n], dst + 8192 * n);
   };
@@ -106,16 +107,17 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int s = 0; s < NS; ++s) qf[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
   }
 
-  // per-lane LDS read offsets (bytes from the start of LDS; stage and block offsets are immediates)
+  // per-lane LDS read addresses into the CURRENT stage of K (koff) and of V (voff), advanced once per tile: every
+  // LDS read is (loop-carried register) + (immediate block offset)
   uint32_t koff[NS];  // K fragment s of key row r (second key block: + 32 rows)
 #pragma unroll
-  for (int s = 0; s < NS; ++s) koff[s] = uint32_t(S::K_OFF + tile_off<D>(r, 2 * s + g));
+  for (int s = 0; s < NS; ++s) koff[s] = lds0 + uint32_t(S::K_OFF + tile_off<D>(r, 2 * s + g));
   uint32_t voff[2][NDB];  // transposing reads of V: rows 4g + li/4 (+8), 16 head-dim columns of block b
 #pragma unroll
   for (int h2 = 0; h2 < 2; ++h2)
 #pragma unroll
     for (int b = 0; b < NDB; ++b)
-      voff[h2][b] = uint32_t(S::V_OFF + tile_off<D>(4 * g + (li >> 2) + 8 * h2, 4 * b + 2 * dh + ((li >> 1) & 1)) +
+      voff[h2][b] = lds0 + uint32_t(S::V_OFF + tile_off<D>(4 * g + (li >> 2) + 8 * h2, 4 * b + 2 * dh + ((li >> 1) & 1)) +
                              8 * (li & 1));
 
   f32x16 acc[NDB];
@@ -125,13 +127,24 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
   float m = -INFINITY, lsum = 0.f;
 
-  // scores of one 32-key block: kb = byte offset of (stage, block) inside the K area
+  auto advance_k = [&](int j) __attribute__((always_inline)) {
+    const int adv = (j % NST) == NST - 1 ? -(NST - 1) * S::TILE : S::TILE;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) koff[s] += adv;
+  };
+  auto advance_v = [&](int j) __attribute__((always_inline)) {
+    const int adv = (j % NST) == NST - 1 ? -(NST - 1) * S::TILE : S::TILE;
+#pragma unroll
+    for (int b = 0; b < NDB; ++b) voff[0][b] += adv, voff[1][b] += adv;
+  };
+
+  // scores of one 32-key block: kb = byte offset of the block inside the current K stage
   auto scores = [&](uint32_t kb, f32x16 &s) __attribute__((always_inline)) {
     bf16x8 ka[NS];
 #pragma unroll
     for (int i = 0; i < 16; ++i) s[i] = 0.f;
 #pragma unroll
-    for (int x = 0; x < NS; ++x) ka[x] = lds_read8(smem + (koff[x] + kb));
+    for (int x = 0; x < NS; ++x) ka[x] = lds_read8_at(koff[x] + kb);
 #pragma unroll
     for (int x = 0; x < NS; ++x) s = mfma32(ka[x], qf[x], s);
   };
@@ -175,14 +188,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       pb[t] = __builtin_bit_cast(bf16x8, w);
     }
   };
-  // vb = byte offset of (stage, block) inside the V area
+  // vb = byte offset of the block inside the current V stage
   auto pv = [&](uint32_t vb, const bf16x8 (&pb)[2]) {
 #pragma unroll
     for (int t = 0; t < 2; ++t) {  // keys 16 t .. 16 t + 15 of the block
 #pragma unroll
       for (int b = 0; b < NDB; ++b) {
-        bf16x8 a = join(lds_read_tr4(smem + (voff[0][b] + vb + 16 * t * ROWB)),
-                        lds_read_tr4(smem + (voff[1][b] + vb + 16 * t * ROWB)));
+        bf16x8 a = join(lds_read_tr4_at(voff[0][b] + vb + 16 * t * ROWB),
+                        lds_read_tr4_at(voff[1][b] + vb + 16 * t * ROWB));
         acc[b] = mfma32(a, pb[t], acc[b]);
       }
     }
@@ -232,19 +245,20 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // Tile j and block 0 of tile j+1 fully visible: no mask, no skip.  After each (rare) rescale there is one
   // basic block with 8 score MFMAs, 16 exponentials, 8 P V MFMAs and a row maximum, all mutually independent
   // except through the bf16 P operands.
-  auto fast = [&](int j, auto st_c) __attribute__((always_inline)) {
-    const int ST = st_c;
+  auto fast = [&](int j) __attribute__((always_inline)) {
     top(j);
     bf16x8 pb[2];
     rescale(mx_cur);
-    scores(uint32_t(ST * S::TILE + 32 * ROWB), nxt);
+    scores(uint32_t(32 * ROWB), nxt);
+    advance_k(j);  // K reads now address tile j+1
     exp_pack(cur, pb);
-    pv(uint32_t(ST * S::TILE), pb);
+    pv(0u, pb);
     mx_nxt = row_max(nxt);
     rescale(mx_nxt);
-    scores(uint32_t(((ST + 1) % NST) * S::TILE), cur);
+    scores(0u, cur);
     exp_pack(nxt, pb);
-    pv(uint32_t(ST * S::TILE + 32 * ROWB), pb);
+    pv(uint32_t(32 * ROWB), pb);
+    advance_v(j);
     mx_cur = row_max(cur);
   };
 
@@ -260,7 +274,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     rescale(row_max(x));
     bf16x8 pb[2];
     exp_pack(x, pb);
-    const uint32_t vb = uint32_t((j % NST) * S::TILE + 32 * kb * ROWB);
+    const uint32_t vb = uint32_t(32 * kb * ROWB);
     pv(vb, pb);
     // The first rows of a document see a handful of keys, their output is as large as a single V row, and
     // the 2^-9 relative rounding of P to bf16 then shows up at the 1e-2 level next to the output's own bf16
@@ -286,18 +300,20 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   auto tail = [&](int j) __attribute__((always_inline)) {
     const int j0 = j * FWD_BN;
     top(j);
-    if (j0 + 32 <= wmax) scores(uint32_t((j % NST) * S::TILE + 32 * ROWB), nxt);
+    if (j0 + 32 <= wmax) scores(uint32_t(32 * ROWB), nxt);
+    advance_k(j);  // K reads now address tile j+1
     tail_block(j, 0, cur);
     if (j + 1 < n_tiles && j0 + FWD_BN <= wmax) {
-      scores(uint32_t(((j + 1) % NST) * S::TILE), cur);
+      scores(0u, cur);
       mx_cur = row_max(cur);
     }
     tail_block(j, 1, nxt);
+    advance_v(j);
   };
 
   for (int j = 0; j < n_tiles; ++j) {
     if (j < n_fast) {
-      fast(j, j & 3);
+      fast(j);
     } else {
       tail(j);
     }
