@@ -31,7 +31,9 @@ __global__ void ca_bwd_prep_kernel(const int32_t *__restrict__ slot_row, const b
                                    float *__restrict__ l2_slot, bf16_t *__restrict__ q_sorted,
                                    bf16_t *__restrict__ do_sorted, int64_t padded, int64_t total_q, int Hq, int D) {
   // D/8 lanes per (slot, head): -Delta = -<dO, O> and log2(e)*LSE in slot order, and the slot-ordered copies of
-  // Q and dO, [head][slot][D] (padding slots: zeros, with an LSE that makes every probability 0)
+  // Q and dO as [block of 64 slots][head][64][D]: the 64-slot tile of a (block, head) is one contiguous run, and
+  // the tiles of the heads of a block follow each other (padding slots: zeros, with an LSE that makes every
+  // probability 0)
   const int lanes = D / 8;
   const int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
   const int64_t pair = idx / lanes;
@@ -53,7 +55,7 @@ __global__ void ca_bwd_prep_kernel(const int32_t *__restrict__ slot_row, const b
   }
   for (int o = lanes / 2; o > 0; o >>= 1) s += __shfl_xor(s, o);
   if (ok) {
-    const size_t so = (size_t(h) * padded + slot) * D + 8 * c;
+    const size_t so = ((size_t(slot / BWD_BQ) * Hq + h) * BWD_BQ + slot % BWD_BQ) * D + 8 * c;
     *reinterpret_cast<u32x4 *>(q_sorted + so) = qv;
     *reinterpret_cast<u32x4 *>(do_sorted + so) = dv;
     if (c == 0) {
@@ -307,8 +309,8 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   const int n_fast = ((u.slot_end - u.slot_full) / BWD_BQ) * G;
 
   // ---- loads of one (q block, head): this wave fetches tile rows RPW*wave .. +RPW-1 of Q and of dO, plus one
-  // 64-float auxiliary array.  Q and dO come from their slot-ordered copies [head][slot][D], in which the tile of a
-  // (block, head) is one contiguous run: a load is (wave-uniform tile address) + (per-lane constant).
+  // 64-float auxiliary array.  Q and dO come from their slot-ordered copies [block][head][64][D], in which the tile
+  // of a (block, head) is one contiguous run: a load is (wave-uniform tile address) + (per-lane constant).
   const int ld_rr = lane / CH;  // row inside one direct load
   uint32_t ld_off[NLD];         // byte offset of the lane's chunk from the start of the tile
 #pragma unroll
@@ -323,8 +325,9 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   // iteration issues the same number of loads, which keeps the s_waitcnt bookkeeping constant.
   int pblk = n_blocks - 1, ph = 0, pst = 0;
   uint32_t pst_addr = lds0;  // LDS address of the stage being filled
-  const int64_t head_stride = padded * D * 2;  // bytes between the tiles of consecutive heads
-  const int64_t tile0 = (int64_t(hk) * G * padded + u.slot_begin + int64_t(pblk) * BWD_BQ) * D * 2;
+  const int64_t head_stride = BWD_BQ * D * 2;            // bytes between the tiles of consecutive heads of a block
+  const int64_t block_stride = int64_t(Hq) * head_stride;  // ... of consecutive blocks, same head
+  const int64_t tile0 = (int64_t(u.slot_begin / BWD_BQ + pblk) * Hq + hk * G) * head_stride;
   const char *q_tile = reinterpret_cast<const char *>(Qs) + tile0, *do_tile = reinterpret_cast<const char *>(dOs) + tile0;
   // the wave's auxiliary array: log2e*LSE (wave 0), -Delta (wave 1), slot positions (wave 2; wave 3 repeats them
   // into a spare area so that every wave issues the same number of loads)
@@ -354,7 +357,7 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
     } else if (pblk > 0) {  // first head of the group, previous block
       ph = 0;
       --pblk;
-      q_tile -= (G - 1) * head_stride + BWD_BQ * D * 2, do_tile -= (G - 1) * head_stride + BWD_BQ * D * 2;
+      q_tile -= (G - 1) * head_stride + block_stride, do_tile -= (G - 1) * head_stride + block_stride;
       aux_ptr -= (G - 1) * aux_hstride + BWD_BQ;
     }  // else: past the end, keep re-fetching the final (block, head)
   };

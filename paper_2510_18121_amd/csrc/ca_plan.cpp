@@ -203,7 +203,7 @@ void schedule(ca_plan_t *p) {
   p->q_covered = covered_q == p->total_q;
   p->kv_covered = covered_kv == p->total_kv;
   // workspace of backward, all in slot order: per (head, slot) fp32 -Delta and log2(e)*LSE, then bf16 copies of Q
-  // and dO as [head][slot][head_dim] (the dK/dV kernel re-reads their 64-slot tiles once per 128-key tile: in this
+  // and dO as [block of 64 slots][head][64][head_dim] (the dK/dV kernel re-reads their 64-slot tiles once per 128-key tile: in this
   // layout a tile is one contiguous run and needs no row indices)
   const size_t per = (size_t(padded) * hq * sizeof(float) + 255) / 256 * 256;
   const size_t copy = (size_t(padded) * hq * p->d * 2 + 255) / 256 * 256;
