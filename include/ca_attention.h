@@ -125,13 +125,18 @@ const char *ca_last_error(void); /* thread-local detail of the last failing call
  * Schedule introspection (host side; for tests, profilers and cost models).
  * ca_plan_info fills `out[0..n)` with, in order: q_tile_rows, n_q_tiles, n_fwd_units, kv_tile_rows,
  * n_bwd_units, fwd_kv_step, padded_rows, sum over forward units of KV steps, sum over backward units of
- * (q blocks x heads) steps, bwd_q_block_rows.  Returns the number of values available.
+ * (q blocks x heads) steps, bwd_q_block_rows, slot_align (a document's rows are padded to this many slots),
+ * heads_packed (query heads per head-packed forward unit).  n_q_tiles counts the full 256-slot tiles.
+ * Returns the number of values available.
  */
 int ca_plan_info(const ca_plan_t *plan, int64_t *out, int n);
 /* Copies of the schedule arrays.  Each returns the element count; pass NULL to query it.
  *  rows : [padded_rows] packed Q row of each tile slot, -1 for padding
  *  pos  : [padded_rows] document position of each tile slot
- *  fwd  : [n_fwd_units][4] = {first slot, packed KV row of doc token 0, keys needed (max pos + 1), head}
+ *  fwd  : [n_fwd_units][5] = {first slot, packed KV row of doc token 0, keys needed (max pos + 1), first head,
+ *                             heads per unit hp}: a unit is one workgroup of the forward and dQ kernels and
+ *                             covers 256 / hp slots of hp consecutive query heads of one KV group; hp = 1 for the
+ *                             full 256-slot tiles of a document, heads_packed for the slots left over
  *  bwd  : [n_bwd_units][7] = {first slot of first q block, slots end, first slot from which every slot sees the
  *                             whole tile, packed KV row of the tile's first key, valid keys in tile, document
  *                             position of the tile's first key, KV head}

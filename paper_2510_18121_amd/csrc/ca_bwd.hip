@@ -104,11 +104,14 @@ __global__ __launch_bounds__(512, 2) void ca_bwd_dq_kernel(const FwdUnit *__rest
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int li = lane & 15, dh = (lane >> 4) & 1;
   const int hk = u.head / (Hq / Hkv);
-  const int slot = u.slot0 + wave * 32 + r;
+  // wave -> (32-slot group, query head) inside the unit, as in the forward kernel
+  const int hp_lg = __builtin_ctz(u.hp);
+  const int head = u.head + (wave & (u.hp - 1));
+  const int slot = u.slot0 + (wave >> hp_lg) * 32 + r;
   const int row = slot_row[slot];
   const int pos = slot_pos[slot];
-  float l2 = l2_slot[int64_t(u.head) * padded + slot];
-  float dl = delta_slot[int64_t(u.head) * padded + slot];
+  float l2 = l2_slot[int64_t(head) * padded + slot];
+  float dl = delta_slot[int64_t(head) * padded + slot];
   const int wmax = wave_max(pos), wmin = wave_min(pos);
   const int n_tiles = (u.n_keys + FWD_BN - 1) / FWD_BN;
   const float c = scale * LOG2E;
@@ -145,7 +148,7 @@ __global__ __launch_bounds__(512, 2) void ca_bwd_dq_kernel(const FwdUnit *__rest
   // Q and dO fragments (B operands); lane holds row's elements 16 s + 8 g .. +7
   bf16x8 qf[NS], dof[NS];
   {
-    const size_t off = (size_t(row < 0 ? 0 : row) * Hq + u.head) * D + 8 * g;
+    const size_t off = (size_t(row < 0 ? 0 : row) * Hq + head) * D + 8 * g;
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       qf[s] = *reinterpret_cast<const bf16x8 *>(Q + off + 16 * s);
@@ -248,7 +251,7 @@ __global__ __launch_bounds__(512, 2) void ca_bwd_dq_kernel(const FwdUnit *__rest
   wait_vmcnt<0>();
 
   if (row >= 0) {
-    bf16_t *op = dQ + (size_t(row) * Hq + u.head) * D + 4 * g;
+    bf16_t *op = dQ + (size_t(row) * Hq + head) * D + 4 * g;
 #pragma unroll
     for (int b = 0; b < NDB; ++b)
 #pragma unroll

@@ -58,7 +58,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int li = lane & 15, dh = (lane >> 4) & 1;
   const int hk = u.head / (Hq / Hkv);
-  const int slot = u.slot0 + wave * 32 + r;
+  // wave -> (32-slot group, query head) inside the unit: hp = 1 for a full tile, > 1 for a head-packed unit
+  const int hp_lg = __builtin_ctz(u.hp);
+  const int head = u.head + (wave & (u.hp - 1));
+  const int slot = u.slot0 + (wave >> hp_lg) * 32 + r;
   const int row = slot_row[slot];
   const int pos = slot_pos[slot];
   const int wmax = wave_max(pos), wmin = wave_min(pos);
@@ -102,7 +105,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // Q fragments: B operand of S^T = K Q^T; lane holds Q[row][16 s + 8 g .. +7]
   bf16x8 qf[NS];
   {
-    const bf16_t *qp = Q + (size_t(row < 0 ? 0 : row) * Hq + u.head) * D + 8 * g;
+    const bf16_t *qp = Q + (size_t(row < 0 ? 0 : row) * Hq + head) * D + 8 * g;
 #pragma unroll
     for (int s = 0; s < NS; ++s) qf[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
   }
@@ -324,7 +327,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   lsum += __shfl_xor(lsum, 32);
   if (row >= 0) {
     const float inv = 1.0f / lsum;
-    bf16_t *op = O + (size_t(row) * Hq + u.head) * D + 4 * g;
+    bf16_t *op = O + (size_t(row) * Hq + head) * D + 4 * g;
 #pragma unroll
     for (int b = 0; b < NDB; ++b)
 #pragma unroll
@@ -333,7 +336,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                    pack_bf16(acc[b][4 * q4 + 2] * inv, acc[b][4 * q4 + 3] * inv)};
         *reinterpret_cast<u32x2 *>(op + 32 * b + 8 * q4) = w;
       }
-    if (g == 0) LSE[size_t(u.head) * total_q + row] = 0.6931471805599453f * (m + fast_log2(lsum));
+    if (g == 0) LSE[size_t(head) * total_q + row] = 0.6931471805599453f * (m + fast_log2(lsum));
   }
 }
 

@@ -9,19 +9,24 @@
 
 namespace ca {
 
-// Tile geometry.  Every document's sorted query rows occupy a run of "slots" padded to SLOT_ALIGN, so
-// that forward tiles (FWD_BM slots) and backward q blocks (BWD_BQ slots) both tile the same arrays.
+// Tile geometry.  Every document's sorted query rows occupy a run of "slots" padded to the plan's slot alignment
+// (at most SLOT_ALIGN), so that forward tiles and backward q blocks (BWD_BQ slots) both tile the same arrays.
 constexpr int SLOT_ALIGN = 256;
 constexpr int FWD_BM = 256;  // query rows per forward work unit (8 waves x 32)
 constexpr int FWD_BN = 64;   // keys per forward inner step
 constexpr int BWD_BN = 128;  // keys owned by one backward work unit (4 waves x 32)
 constexpr int BWD_BQ = 64;   // query rows per backward inner step
 
-struct FwdUnit {  // one (q tile, q head)
-  int32_t slot0;    // first slot of the tile
+// One workgroup of the forward / dQ kernels: 8 waves of 32 slots each.  A full tile of a document is 256 slots of
+// one query head (hp = 1).  The slots a document has left over after its full tiles are covered by head-packed units
+// instead: 256 / hp slots of hp consecutive query heads of one KV group (they read the same K/V), wave w taking
+// slots slot0 + 32 (w / hp) .. of head  head + w % hp  - so that short documents keep all 8 waves busy too.
+struct FwdUnit {
+  int32_t slot0;    // first slot of the unit
   int32_t kv_row0;  // packed KV row of the document's token 0
-  int32_t n_keys;   // keys the tile needs: max position + 1
-  int32_t head;
+  int32_t n_keys;   // keys the unit needs: max position + 1
+  int32_t head;     // first query head
+  int32_t hp;       // query heads per unit: 1, 2, 4 or 8
 };
 
 struct BwdUnit {  // one (KV tile, KV head)
@@ -49,6 +54,7 @@ struct ca_plan {
   std::vector<ca::BwdUnit> bwd_units;
   int64_t fwd_steps = 0, bwd_steps = 0;
   // workspace layout for backward: [Delta fp32 hq*padded_slots][log2e*LSE fp32 hq*padded_slots]
+  int slot_align = ca::SLOT_ALIGN, heads_packed = 1;  // padding of a document's slots; hp of the packed units
   size_t ws_fwd = 0, ws_bwd = 0, ws_off_l2 = 0, ws_off_qs = 0, ws_off_dos = 0;
   bool q_covered = false, kv_covered = false;  // every packed Q row / KV row belongs to some unit
   // device copies

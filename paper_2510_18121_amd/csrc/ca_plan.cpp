@@ -100,11 +100,18 @@ void schedule(ca_plan_t *p) {
   // tasks of each document, by position
   std::vector<std::vector<int32_t>> by_doc(p->n_docs);
   for (int t = 0; t < p->n_tasks; ++t) by_doc[p->task_doc[t]].push_back(t);
+  // heads packed into the units of partial tiles: the largest of 8, 4, 2, 1 that divides the group size; a document's
+  // slots are padded to whole packed units (and to whole backward q blocks)
+  const int hp = g % 8 == 0 ? 8 : g % 4 == 0 ? 4 : g % 2 == 0 ? 2 : 1;
+  const int sub = FWD_BM / hp;  // slots of a packed unit
+  const int align = std::max(sub, BWD_BQ);
+  p->heads_packed = hp;
+  p->slot_align = align;
   int64_t padded = 0;
   for (auto &v : by_doc) {
     int64_t n = 0;
     for (int t : v) n += p->task_q_len[t];
-    padded += round_up(n, SLOT_ALIGN);
+    padded += round_up(n, align);
   }
   CA_REQUIRE(padded < (int64_t(1) << 31) - SLOT_ALIGN, CA_ERR_UNSUPPORTED, "too many padded query rows");
   p->slot_row.assign(padded, -1);
@@ -142,14 +149,20 @@ void schedule(ca_plan_t *p) {
       for (int64_t i = s0; i < s; ++i) p->slot_pos[i] = rows[i - s0].pos, p->slot_row[i] = rows[i - s0].row;
     }
     const int32_t last_pos = p->slot_pos[s - 1];
-    const int64_t s1 = round_up(s, SLOT_ALIGN);
+    const int64_t s1 = round_up(s - s0, align) + s0;
     for (; s < s1; ++s) p->slot_pos[s] = last_pos;  // padding slots: row -1, position of the last real row
     const int32_t kv_row0 = int32_t(p->doc_kv_start[dd]);
-    // forward tiles
-    for (int64_t a = s0; a < s1; a += FWD_BM) {
-      if (p->slot_row[a] < 0) break;  // tile of pure padding
+    // forward units: full tiles of 256 slots, then head-packed units over the rest
+    int64_t a = s0;
+    for (; a + FWD_BM <= s1; a += FWD_BM) {
+      if (p->slot_row[a] < 0) break;  // pure padding
       int32_t n_keys = p->slot_pos[a + FWD_BM - 1] + 1;
-      ftiles.push_back({(n_keys + FWD_BN - 1) / FWD_BN, {int32_t(a), kv_row0, n_keys, 0}});
+      ftiles.push_back({(n_keys + FWD_BN - 1) / FWD_BN, {int32_t(a), kv_row0, n_keys, 0, 1}});
+    }
+    for (; a < s1; a += sub) {
+      if (p->slot_row[a] < 0) break;  // pure padding
+      int32_t n_keys = p->slot_pos[a + sub - 1] + 1;
+      ftiles.push_back({(n_keys + FWD_BN - 1) / FWD_BN, {int32_t(a), kv_row0, n_keys, 0, int32_t(hp)}});
     }
     // backward KV tiles: every resident key of the document.  Keys beyond the last query position get a
     // unit without query blocks, which writes their zero gradient.
@@ -182,9 +195,9 @@ void schedule(ca_plan_t *p) {
   p->fwd_units.reserve(ftiles.size() * hq);
   p->fwd_steps = 0;
   for (auto &t : ftiles)
-    for (int i = 0; i < hq; ++i) {
+    for (int i = 0; i < hq / t.u.hp; ++i) {  // KV heads fastest; inside a KV head, its groups of hp query heads
       FwdUnit u = t.u;
-      u.head = (i % hkv) * g + i / hkv;
+      u.head = (i % hkv) * g + (i / hkv) * u.hp;
       p->fwd_units.push_back(u);
       p->fwd_steps += t.cost;
     }
@@ -286,11 +299,13 @@ int ca_plan_workspace_bytes(const ca_plan_t *p, size_t *fwd, size_t *bwd) {
 
 int ca_plan_info(const ca_plan_t *p, int64_t *out, int n) {
   if (!p) return 0;
-  const int64_t v[10] = {ca::FWD_BM, int64_t(p->fwd_units.size() / (p->hq ? p->hq : 1)), int64_t(p->fwd_units.size()),
+  int64_t full_tiles = 0;
+  for (auto &u : p->fwd_units) full_tiles += u.hp == 1 && u.head == 0;
+  const int64_t v[12] = {ca::FWD_BM, full_tiles, int64_t(p->fwd_units.size()),
                          ca::BWD_BN, int64_t(p->bwd_units.size()), ca::FWD_BN, int64_t(p->slot_row.size()),
-                         p->fwd_steps, p->bwd_steps, ca::BWD_BQ};
-  for (int i = 0; i < n && i < 10 && out; ++i) out[i] = v[i];
-  return 10;
+                         p->fwd_steps, p->bwd_steps, ca::BWD_BQ, p->slot_align, p->heads_packed};
+  for (int i = 0; i < n && i < 12 && out; ++i) out[i] = v[i];
+  return 12;
 }
 
 int64_t ca_plan_rows(const ca_plan_t *p, int32_t *rows, int32_t *pos) {

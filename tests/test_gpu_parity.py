@@ -37,10 +37,11 @@ def test_downscaled_twins_full_tensors(idx, div):
 RAGGED = [1, 2, 15, 17, 31, 33, 63, 65, 127, 129, 255, 257, 300]
 
 
-@pytest.mark.parametrize("d,hq,hkv", [(64, 4, 2), (128, 4, 4), (128, 8, 1)])
+@pytest.mark.parametrize("d,hq,hkv", [(64, 4, 2), (128, 4, 4), (128, 8, 1), (128, 8, 2), (64, 6, 2)])
 def test_ragged_shards_and_head_layouts(d, hq, hkv):
     """One document cut at ragged points (1-row shards included), shards shuffled in packed Q, next to a
-    one-token document and a document cut in two; MHA, GQA 2 and GQA 8."""
+    one-token document and a document cut in two; MHA and GQA 2, 8, 4 and 3: the slots left over after a document's
+    full tiles go to units of 1, 2, 8, 4 and 1 heads."""
     tasks, a = [], 0
     for n in RAGGED:
         tasks.append((0, a, n))

@@ -83,7 +83,9 @@ def check_schedule(b):
     rows, pos = p.rows()
     bm, bq, bn = info["q_tile_rows"], info["bwd_q_block_rows"], info["kv_tile_rows"]
     g = b.n_q_heads // b.n_kv_heads
-    assert len(rows) == info["padded_rows"] and len(rows) % bm == 0
+    al, hp = info["slot_align"], info["heads_packed"]
+    assert hp == max(k for k in (8, 4, 2, 1) if g % k == 0) and al == max(bm // hp, bq)
+    assert len(rows) == info["padded_rows"] and len(rows) % al == 0
     # every packed query row of every task sits in exactly one slot, with its document position
     want_pos = np.full(b.total_q, -1, np.int64)
     want_doc = np.full(b.total_q, -1, np.int64)
@@ -94,16 +96,21 @@ def check_schedule(b):
     real = rows >= 0
     assert sorted(rows[real].tolist()) == np.flatnonzero(want_pos >= 0).tolist()
     assert np.array_equal(pos[real], want_pos[rows[real]])
-    # forward units
+    # forward units: a full tile is bm slots of one head, a head-packed unit bm / hp slots of hp heads of one KV group
     fu = p.fwd_units()
-    assert len(fu) == info["n_fwd_units"] == info["n_q_tiles"] * b.n_q_heads
+    assert fu.shape == (info["n_fwd_units"], 5)
+    assert info["n_q_tiles"] == len(set(fu[(fu[:, 4] == 1) | (hp == 1), 0].tolist()))
     costs = -(-fu[:, 2] // info["fwd_kv_step"])
     assert np.all(np.diff(costs) <= 0), "longest first"
-    seen = set()
-    for i, (s0, kv0, nk, h) in enumerate(fu.tolist()):
-        assert s0 % bm == 0 and 0 <= h < b.n_q_heads
+    head_cover = np.zeros((len(rows), b.n_q_heads), np.int32)
+    for i, (s0, kv0, nk, h, k) in enumerate(fu.tolist()):
+        assert k in (1, hp) and h % k == 0 and 0 <= h and h + k <= b.n_q_heads
+        assert h // g == (h + k - 1) // g, "the heads of a unit share their KV head"
+        span = bm // k
+        assert s0 % span == 0 or k == 1
         assert (i % b.n_kv_heads) == h // g, "unit index modulo n_kv_heads is the KV head"
-        tile_rows, tile_pos = rows[s0:s0 + bm], pos[s0:s0 + bm]
+        tile_rows, tile_pos = rows[s0:s0 + span], pos[s0:s0 + span]
+        assert len(tile_rows) == span, "a unit never reaches past the padded slots"
         ok = tile_rows >= 0
         assert ok.any() and ok[0]
         docs = set(want_doc[tile_rows[ok]].tolist())
@@ -112,12 +119,9 @@ def check_schedule(b):
         assert kv0 == b.doc_kv_start[dd] and nk == tile_pos[ok].max() + 1
         assert np.all(np.diff(tile_pos) >= 0), "slots sorted by position"
         assert np.all(tile_pos[~ok] == tile_pos[ok][-1])
-        seen.add((s0, h))
-    assert len(seen) == len(fu)
-    covered = np.zeros(len(rows), bool)
-    for s0 in set(fu[:, 0].tolist()):
-        covered[s0:s0 + bm] = True
-    assert np.all(covered[real])
+        head_cover[s0:s0 + span, h:h + k] += 1
+    assert head_cover.max() <= 1, "no (slot, head) belongs to two units"
+    assert np.all(head_cover[real] == 1), "every real (slot, head) belongs to one unit"
     # backward units: every key of every scheduled document once per KV head
     bu = p.bwd_units()
     assert len(bu) == info["n_bwd_units"]
@@ -156,6 +160,11 @@ def test_schedule_invariants_small_and_ragged():
     # single-row tasks, a document with no task, gaps in positions
     b = W.custom([5, 9, 700], [(0, 4, 1), (2, 0, 1), (2, 300, 1), (2, 650, 50)], 4, 4, 64, doc_order=[2, 0, 1])
     check_schedule(b)
+    # every packing factor: group sizes 8, 4, 2, 1 and 3 -> 8, 4, 2, 1 and 1 heads per unit of the left-over slots
+    for hq, hkv in ((8, 1), (16, 2), (8, 2), (4, 2), (4, 4), (6, 2)):
+        b = W.custom([40, 300, 1000, 257], [(0, 0, 40), (1, 0, 300), (2, 100, 333), (2, 600, 400), (3, 0, 257)], hq, hkv, 64)
+        info = check_schedule(b).info()
+        assert info["heads_packed"] == {8: 8, 4: 4, 2: 2, 1: 1, 3: 1}[hq // hkv]
 
 
 @pytest.mark.parametrize("idx", [2, 3, 4, 5])
