@@ -49,6 +49,7 @@ def _load():
         _lib.ca_oracle_forward.restype = ctypes.c_int
         _lib.ca_oracle_backward.restype = ctypes.c_int
         _lib.ca_oracle_threads.restype = ctypes.c_int
+        _lib.ca_oracle_merge.restype = ctypes.c_int
     return _lib
 
 
@@ -132,3 +133,23 @@ def forward_backward(batch, q, k, v, d_o, want=("dq", "dk", "dv")):
     o, lse = forward(batch, q, k, v)
     dq, dk, dv, delta = backward(batch, q, k, v, o, d_o, lse, want)
     return {"o": o, "lse": lse, "dq": dq, "dk": dk, "dv": dv, "delta": delta}
+
+
+def merge_partials(part_rows, o_part, lse_part):
+    """Combine partial results over disjoint key sets: part_rows [n_parts, n_rows] (row in the partial buffers,
+    -1 = no such part), o_part [total_q_part, Hq, D], lse_part [Hq, total_q_part] -> O [n_rows, Hq, D], LSE [Hq, n_rows]."""
+    lib = _load()
+    pr = np.ascontiguousarray(np.asarray(part_rows), dtype=np.int64)
+    n_parts, n_rows = pr.shape
+    o_part = np.ascontiguousarray(np.asarray(o_part, dtype=np.float64))
+    tq, hq, d = o_part.shape
+    lse_part = _f64(lse_part, (hq, tq))
+    if pr.size and (pr.max() >= tq or pr.min() < -1):
+        raise ValueError("part_rows outside the partial buffers")
+    o = np.full((n_rows, hq, d), np.nan)
+    lse = np.full((hq, n_rows), np.nan)
+    rc = lib.ca_oracle_merge(ctypes.c_int64(n_rows), ctypes.c_int32(n_parts), _ptr(pr), _ptr(o_part), _ptr(lse_part),
+                             ctypes.c_int64(tq), ctypes.c_int32(hq), ctypes.c_int32(d), _ptr(o), _ptr(lse))
+    if rc != 0:
+        raise RuntimeError(f"ca_oracle_merge failed: {rc}")
+    return o, lse

@@ -11,6 +11,9 @@
  *   - the row at document position p sees keys 0..p of its own document, diagonal included;
  *     this is the reading under which a shard's work is proportional to n_q(2 n_kv - n_q)
  *     with n_q + L_kv - L_q <= n_kv <= L_kv (Appendix B);
+ *   - a task may name fewer keys than that (kv_len < p + 1): the row then sees keys 0..kv_len-1 only.  With a
+ *     "document" that is a window of a longer context this is a query shard attending a sub-range of its
+ *     context (the extension named in the Limitations section); ca_oracle_merge combines such partial results;
  *   - the backward is the calculus of that definition for the scalar sum(dO * O), with P
  *     recomputed from the per-row log-sum-exp rather than stored (Section 2.1: P is not
  *     materialised, it is recomputed during backward).
@@ -175,5 +178,50 @@ int ca_oracle_backward(const ca_oracle_batch *b, const double *Q, const double *
   }
   if (Delta_out) memcpy(Delta_out, Delta, sizeof(double) * (size_t)(Hq * b->total_q));
   free(Delta);
+  return 0;
+}
+
+/*
+ * Merge of partial results (the Limitations section names a query shard that attends only a sub-range of its
+ * context as the extension of the CA-task; the partial outputs of one row over disjoint key sets K_1..K_n then have
+ * to be combined).
+ * From the definition: with L_i = log sum_{j in K_i} exp(s_j) and O_i = sum_{j in K_i} exp(s_j - L_i) V_j,
+ *   L = log sum_i exp(L_i),   O = sum_i exp(L_i - L) O_i
+ * is the softmax-weighted sum over the union of the key sets.
+ * part_rows[i * n_rows + r] is the row of part i of merged row r in the partial buffers, or -1 if the row has no such
+ * part.  O_part [total_q_part][Hq][D], LSE_part [Hq][total_q_part]; O [n_rows][Hq][D], LSE [Hq][n_rows].
+ * A row without any part gets O = 0 and LSE = -infinity.
+ */
+int ca_oracle_merge(int64_t n_rows, int32_t n_parts, const int64_t *part_rows, const double *O_part,
+                    const double *LSE_part, int64_t total_q_part, int32_t Hq, int32_t D, double *O, double *LSE) {
+  for (int64_t r = 0; r < n_rows; ++r) {
+    for (int h = 0; h < Hq; ++h) {
+      double m = -INFINITY;
+      for (int i = 0; i < n_parts; ++i) {
+        const int64_t pr = part_rows[(int64_t)i * n_rows + r];
+        if (pr >= 0 && LSE_part[(int64_t)h * total_q_part + pr] > m) m = LSE_part[(int64_t)h * total_q_part + pr];
+      }
+      double *o = O + (r * Hq + h) * D;
+      for (int d = 0; d < D; ++d) o[d] = 0.0;
+      if (m == -INFINITY) {
+        LSE[(int64_t)h * n_rows + r] = -INFINITY;
+        continue;
+      }
+      double sum = 0.0;
+      for (int i = 0; i < n_parts; ++i) {
+        const int64_t pr = part_rows[(int64_t)i * n_rows + r];
+        if (pr >= 0) sum += exp(LSE_part[(int64_t)h * total_q_part + pr] - m);
+      }
+      const double l = m + log(sum);
+      for (int i = 0; i < n_parts; ++i) {
+        const int64_t pr = part_rows[(int64_t)i * n_rows + r];
+        if (pr < 0) continue;
+        const double w = exp(LSE_part[(int64_t)h * total_q_part + pr] - l);
+        const double *op = O_part + (pr * Hq + h) * D;
+        for (int d = 0; d < D; ++d) o[d] += w * op[d];
+      }
+      LSE[(int64_t)h * n_rows + r] = l;
+    }
+  }
   return 0;
 }

@@ -56,7 +56,8 @@ class Batch:
 
     def pairs(self) -> int:
         """Exact number of (query row, visible key) pairs, diagonal included."""
-        return int(sum(task_pairs(int(a), int(n)) for a, n in zip(self.task_q_pos, self.task_q_len)))
+        return int(sum(task_pairs(int(a), int(n), int(kv))
+                       for a, n, kv in zip(self.task_q_pos, self.task_q_len, self.task_kv_len)))
 
     def flops(self) -> dict:
         """Causal FLOPs: 2 contractions forward, 5 backward, 2 flops per multiply-add."""
@@ -66,9 +67,13 @@ class Batch:
         return {"pairs": p, "fwd": f, "bwd": b, "total": f + b}
 
 
-def task_pairs(q_pos: int, q_len: int) -> int:
-    """Pairs of a shard whose first query sits at document position q_pos: sum_{p}(p+1)."""
-    return q_len * (2 * q_pos + q_len + 1) // 2
+def task_pairs(q_pos: int, q_len: int, kv_len: int | None = None) -> int:
+    """Pairs of a shard whose first query sits at document position q_pos: sum over its rows p of min(kv_len, p + 1)
+    (kv_len None or >= q_pos + q_len: the full causal prefix, sum_p (p + 1))."""
+    if kv_len is None or kv_len >= q_pos + q_len:
+        return q_len * (2 * q_pos + q_len + 1) // 2
+    c = max(0, kv_len - q_pos)  # rows that still see their whole prefix
+    return c * (2 * q_pos + c + 1) // 2 + (q_len - c) * kv_len
 
 
 def _mk(name, hq, hkv, d, doc_lens, doc_order, tasks, task_order, seed, meta=None) -> Batch:
@@ -231,6 +236,63 @@ def shard_chunk(shard_len: int, mode: str = "distinct", seed: int = 0, chunk_tok
     order = rng.permutation(len(tasks)).tolist()
     return _mk(f"shard_chunk_{mode}_{shard_len}", hq, hkv, d, doc_lens, list(range(len(doc_lens))), tasks, order,
                seed, {"shard_len": shard_len, "mode": mode})
+
+
+def split_kv(b: Batch, window: int):
+    """Cut every document's keys into windows of `window` tokens and every CA-task into one partial task per window
+    it can see (a query shard attending a sub-range of its context: the extension named in the paper's Limitations
+    section).  Pure bookkeeping: the packed K/V buffers stay as they are (a window is a sub-range of its document's
+    rows and becomes a "document" of the new batch, positions counted from the window's first key); the query rows
+    of a partial task are copies of the original rows.
+
+    Returns (partial batch, gather, part_rows): gather [total_q'] = original packed-Q row of every row of the
+    partial batch (to build its Q and dO, and to scatter results back); part_rows [n_parts, total_q] int32 = for every
+    original row its rows in the partial batch, window by window, -1 where it has fewer windows.
+    """
+    assert window >= 1
+    doc_start, doc_len, win_of_doc = [], [], []
+    for dd in range(b.n_docs):
+        ids = []
+        for c in range(0, int(b.doc_kv_len[dd]), window):
+            ids.append(len(doc_start))
+            doc_start.append(int(b.doc_kv_start[dd]) + c)
+            doc_len.append(min(window, int(b.doc_kv_len[dd]) - c))
+        win_of_doc.append(ids)
+    t_doc, t_start, t_len, t_pos, t_kv, gather = [], [], [], [], [], []
+    n_parts = 1
+    for t in range(b.n_tasks):
+        a, n, kv = int(b.task_q_pos[t]), int(b.task_q_len[t]), int(b.task_kv_len[t])
+        n_parts = max(n_parts, -(-min(kv, a + n) // window))
+    part_rows = np.full((n_parts, b.total_q), -1, np.int32)
+    off = 0
+    for t in range(b.n_tasks):
+        dd, a, n, kv = int(b.task_doc[t]), int(b.task_q_pos[t]), int(b.task_q_len[t]), int(b.task_kv_len[t])
+        q0 = int(b.task_q_start[t])
+        for w, wid in enumerate(win_of_doc[dd]):
+            c = w * window
+            if c >= min(kv, a + n):
+                break  # no row of the task sees a key of this window
+            first = max(a, c)  # first position that sees the window's first key
+            m = a + n - first
+            t_doc.append(wid)
+            t_start.append(off)
+            t_len.append(m)
+            t_pos.append(first - c)
+            t_kv.append(min(c + window, kv, int(b.doc_kv_len[dd])) - c)
+            rows = np.arange(q0 + first - a, q0 + n)
+            gather.append(rows)
+            part_rows[w, rows] = off + np.arange(m)
+            off += m
+    nb = Batch(
+        name=b.name + f"_kvsplit{window}", n_q_heads=b.n_q_heads, n_kv_heads=b.n_kv_heads, head_dim=b.head_dim,
+        total_q=off, total_kv=b.total_kv, doc_kv_start=np.asarray(doc_start, np.int64),
+        doc_kv_len=np.asarray(doc_len, np.int64), task_doc=np.asarray(t_doc, np.int32),
+        task_q_start=np.asarray(t_start, np.int64), task_q_len=np.asarray(t_len, np.int64),
+        task_q_pos=np.asarray(t_pos, np.int64), task_kv_len=np.asarray(t_kv, np.int64),
+        softmax_scale=b.scale, seed=b.seed, meta={**b.meta, "kv_window": window},
+    )
+    g = np.concatenate(gather) if gather else np.zeros(0, np.int64)
+    return nb, g.astype(np.int64), part_rows
 
 
 def config(index: int, downscale: int = 1) -> Batch:
