@@ -26,6 +26,14 @@
  * n_q + L_kv - L_q <= n_kv <= L_kv).  Tasks of one document share that document's single KV range;
  * dK/dV are gradients with respect to the packed KV buffer (summed over all tasks and all query heads
  * of a group); KV rows no query attends receive 0.
+ *
+ * Query shard with a SUB-RANGE of its context (the extension named in the paper's Limitations section): declare
+ * the key window [lo, hi) of the context as a "document" (doc_kv_start = row of key lo, doc_kv_len = hi - lo) and
+ * the shard as a task on it with q_pos counted from lo and kv_len <= hi - lo.  kv_len may be smaller than
+ * q_pos + q_len: rows beyond it see the whole window.  Each (shard, window) task has query rows of its own (copies
+ * of the shard's Q and dO).  ca_forward then yields partial O and LSE; ca_merge_partials combines the partial
+ * results of a row; ca_backward on the partial tasks, given the MERGED O and LSE in their rows, yields the whole
+ * dK, dV of each window and partial dQ that ca_sum_partial_dq adds up.
  */
 #ifndef CA_ATTENTION_H
 #define CA_ATTENTION_H
@@ -39,7 +47,7 @@ extern "C" {
 
 typedef enum {
   CA_OK = 0,
-  CA_ERR_INVALID_ARG = -1, /* null pointer, bad count, range out of bounds, overlapping ranges, q_pos+q_len > kv_len ... */
+  CA_ERR_INVALID_ARG = -1, /* null pointer, bad count, range out of bounds, overlapping ranges, kv_len < 1 ... */
   CA_ERR_UNSUPPORTED = -2, /* head_dim not in {64,128}, n_q_heads not a multiple of n_kv_heads, sizes beyond int32 tiles */
   CA_ERR_WORKSPACE = -3,   /* workspace null, too small or not 256-byte aligned */
   CA_ERR_HIP = -4,         /* a HIP runtime call failed; detail string has its name and message */
@@ -60,7 +68,8 @@ typedef struct {
   const int64_t *task_q_start;             /* [n_tasks] first row in packed Q */
   const int64_t *task_q_len;               /* [n_tasks] n_q >= 1, any integer */
   const int64_t *task_q_pos;               /* [n_tasks] document position of the first query row */
-  const int64_t *task_kv_len;              /* [n_tasks] prefix attended: q_pos+q_len <= kv_len <= doc_kv_len */
+  const int64_t *task_kv_len;              /* [n_tasks] keys attended: 1 <= kv_len <= doc_kv_len; q_pos + q_len for
+                                              the plain causal prefix, less to clip the shard to a key window */
 } ca_batch_desc;
 
 /*
@@ -105,6 +114,32 @@ int ca_backward(const ca_plan_t *plan, const void *q, const void *k, const void 
                 void *ws, size_t ws_bytes, void *hip_stream);
 
 void ca_plan_destroy(ca_plan_t *plan);
+
+/*
+ * ca_merge_partials: combine partial attention results of query rows over disjoint key sets (Limitations section:
+ * a query shard may attend a sub-range of its context; the results over the sub-ranges then have to be merged).
+ * With L_i the log-sum-exp and O_i the output of part i:  L = log sum_i exp(L_i),  O = sum_i exp(L_i - L) O_i.
+ * part_rows: DEVICE int32 [n_parts][n_rows]; part_rows[i][r] = row of part i of merged row r in the partial buffers,
+ *   or -1 (or any value outside [0, total_q_part)) if the row has no such part.  A partial row may belong to one merged
+ *   row only.
+ * o_part: device bf16 [total_q_part][n_q_heads][head_dim]; lse_part: device fp32 [n_q_heads][total_q_part].
+ * o: device bf16 [n_rows][n_q_heads][head_dim]; lse: device fp32 [n_q_heads][n_rows] (merged results; a row without
+ *   parts gets O = 0, LSE = -inf).
+ * o_back, lse_back: NULL, or buffers shaped like o_part / lse_part that receive the merged O and LSE in every partial
+ *   row (what ca_backward needs for the partial tasks); they may be o_part and lse_part themselves (in place).
+ * 1 <= n_parts <= 64.  One launch on `hip_stream`; allocates nothing, never synchronises.
+ */
+int ca_merge_partials(const int32_t *part_rows, int64_t n_rows, int32_t n_parts, const void *o_part,
+                      const float *lse_part, int64_t total_q_part, void *o, float *lse, void *o_back,
+                      float *lse_back, int32_t n_q_heads, int32_t head_dim, void *hip_stream);
+
+/*
+ * ca_sum_partial_dq: dq[r] = sum over the parts i of row r of dq_part[part_rows[i][r]] (fp32 sum of the bf16
+ * partial gradients, rounded once): the query gradient of a row whose context was cut into key windows.
+ * Arguments as in ca_merge_partials; dq: device bf16 [n_rows][n_q_heads][head_dim]; rows without parts get 0.
+ */
+int ca_sum_partial_dq(const int32_t *part_rows, int64_t n_rows, int32_t n_parts, const void *dq_part,
+                      int64_t total_q_part, void *dq, int32_t n_q_heads, int32_t head_dim, void *hip_stream);
 
 /*
  * Per-kernel timing for profilers and cost models (Section 4.2's profiler benchmarks core attention over

@@ -65,6 +65,9 @@ def lib() -> ctypes.CDLL:
         L.ca_plan_rows.argtypes = [vp, vp, vp]
         L.ca_plan_fwd_units.argtypes = [vp, vp]
         L.ca_plan_bwd_units.argtypes = [vp, vp]
+        i32, i64 = ctypes.c_int32, ctypes.c_int64
+        L.ca_merge_partials.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, vp, vp, i32, i32, vp]
+        L.ca_sum_partial_dq.argtypes = [vp, i64, i32, vp, i64, vp, i32, i32, vp]
         _lib = L
     return _lib
 
@@ -225,3 +228,34 @@ def alloc_workspace(plan: Plan, device="cuda"):
     import torch
     f, b = plan.workspace_bytes()
     return torch.empty(max(f, b, 256), dtype=torch.uint8, device=device)
+
+
+def ca_merge_partials(part_rows, o_part, lse_part, o, lse, o_back=None, lse_back=None, stream=None):
+    """Merge partial results over disjoint key windows.  part_rows: device int32 [n_parts, n_rows]; o_part bf16
+    [total_q_part, Hq, D], lse_part fp32 [Hq, total_q_part]; writes o bf16 [n_rows, Hq, D] and lse fp32 [Hq, n_rows];
+    o_back / lse_back (may be o_part / lse_part) receive the merged values in every partial row."""
+    import torch
+    n_parts, n_rows = part_rows.shape
+    tq, hq, d = o_part.shape
+    _expect(part_rows, (n_parts, n_rows), torch.int32, "part_rows")
+    _expect(o_part, (tq, hq, d), torch.bfloat16, "o_part")
+    _expect(lse_part, (hq, tq), torch.float32, "lse_part")
+    _expect(o, (n_rows, hq, d), torch.bfloat16, "o")
+    _expect(lse, (hq, n_rows), torch.float32, "lse")
+    if o_back is not None:
+        _expect(o_back, (tq, hq, d), torch.bfloat16, "o_back")
+    if lse_back is not None:
+        _expect(lse_back, (hq, tq), torch.float32, "lse_back")
+    _check(lib().ca_merge_partials(_p(part_rows), n_rows, n_parts, _p(o_part), _p(lse_part), tq, _p(o), _p(lse),
+                                   _p(o_back), _p(lse_back), hq, d, _stream_ptr(stream)))
+
+
+def ca_sum_partial_dq(part_rows, dq_part, dq, stream=None):
+    """dq[r] = sum of the partial query gradients of row r (arguments as in ca_merge_partials)."""
+    import torch
+    n_parts, n_rows = part_rows.shape
+    tq, hq, d = dq_part.shape
+    _expect(part_rows, (n_parts, n_rows), torch.int32, "part_rows")
+    _expect(dq_part, (tq, hq, d), torch.bfloat16, "dq_part")
+    _expect(dq, (n_rows, hq, d), torch.bfloat16, "dq")
+    _check(lib().ca_sum_partial_dq(_p(part_rows), n_rows, n_parts, _p(dq_part), tq, _p(dq), hq, d, _stream_ptr(stream)))

@@ -78,9 +78,8 @@ void validate(const ca_batch_desc *d) {
     CA_REQUIRE(d->task_q_start[t] >= 0 && d->task_q_start[t] <= d->total_q - d->task_q_len[t], CA_ERR_INVALID_ARG,
                "task " << t << " query range outside packed Q of " << d->total_q << " rows");
     CA_REQUIRE(d->task_q_pos[t] >= 0, CA_ERR_INVALID_ARG, "task " << t << " has negative q_pos");
-    CA_REQUIRE(d->task_q_pos[t] + d->task_q_len[t] <= d->task_kv_len[t], CA_ERR_INVALID_ARG,
-               "task " << t << ": q_pos + q_len = " << d->task_q_pos[t] + d->task_q_len[t] << " exceeds kv_len "
-                       << d->task_kv_len[t] << " (a query row must see itself)");
+    CA_REQUIRE(d->task_kv_len[t] >= 1, CA_ERR_INVALID_ARG,
+               "task " << t << " has kv_len " << d->task_kv_len[t] << " (every row must see at least one key)");
     CA_REQUIRE(d->task_kv_len[t] <= d->doc_kv_len[d->task_doc[t]], CA_ERR_INVALID_ARG,
                "task " << t << ": kv_len " << d->task_kv_len[t] << " exceeds its document's resident KV "
                        << d->doc_kv_len[d->task_doc[t]]);
@@ -134,15 +133,15 @@ void schedule(ca_plan_t *p) {
       int32_t pos, row;
     };
     const int64_t s0 = s;
-    bool sorted = true;
-    for (size_t i = 1; i < v.size(); ++i)
-      if (p->task_q_pos[v[i]] < p->task_q_pos[v[i - 1]] + p->task_q_len[v[i - 1]]) sorted = false;
+    // a slot's "position" is the last key its row sees: min(document position, kv_len - 1); a task with a prefix
+    // shorter than its rows' positions (a shard attending a window of its context) is thereby clipped to the window
     for (int t : v)
       for (int64_t i = 0; i < p->task_q_len[t]; ++i, ++s) {
         p->slot_row[s] = int32_t(p->task_q_start[t] + i);
-        p->slot_pos[s] = int32_t(p->task_q_pos[t] + i);
+        p->slot_pos[s] = int32_t(std::min(p->task_q_pos[t] + i, p->task_kv_len[t] - 1));
       }
-    if (!sorted) {  // rare: tasks of one document covering the same positions twice
+    const bool sorted = std::is_sorted(p->slot_pos.begin() + s0, p->slot_pos.begin() + s);
+    if (!sorted) {  // rare: tasks of one document covering the same positions twice, or clipped below earlier tasks
       std::vector<Row> rows(s - s0);
       for (int64_t i = s0; i < s; ++i) rows[i - s0] = {p->slot_pos[i], p->slot_row[i]};
       std::stable_sort(rows.begin(), rows.end(), [](const Row &a, const Row &b) { return a.pos < b.pos; });

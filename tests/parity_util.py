@@ -37,6 +37,42 @@ def run_hip(batch, q, k, v, d_o=None, plan=None):
     return out
 
 
+def run_hip_kv_split(batch, window, q, k, v, d_o=None, in_place=True):
+    """The same results by way of key windows: every task cut into one partial task per `window` keys of its context,
+    one fused forward over all partial tasks, ca_merge_partials, and (when d_o is given) ca_backward on the partial
+    tasks with the merged O and LSE in their rows, then ca_sum_partial_dq.  Index plumbing (gathering the copies of
+    Q and dO) is torch; every arithmetic step is a library call."""
+    pb, gather, part_rows = W.split_kv(batch, window)
+    dev = q.device
+    g = torch.as_tensor(gather, device=dev)
+    pr = torch.as_tensor(part_rows, device=dev).contiguous()
+    qp = q.index_select(0, g).contiguous()
+    plan = B.ca_plan(pb)
+    ws = B.alloc_workspace(plan, dev)
+    o_p = torch.full_like(qp, float("nan"))
+    lse_p = torch.full((pb.n_q_heads, pb.total_q), float("nan"), dtype=torch.float32, device=dev)
+    B.ca_forward(plan, qp, k, v, o_p, lse_p, ws)
+    o = torch.full_like(q, float("nan"))
+    lse = torch.full((batch.n_q_heads, batch.total_q), float("nan"), dtype=torch.float32, device=dev)
+    if in_place:
+        o_b, lse_b = o_p, lse_p
+    else:
+        o_b, lse_b = torch.full_like(o_p, float("nan")), torch.full_like(lse_p, float("nan"))
+    B.ca_merge_partials(pr, o_p, lse_p, o, lse, o_b if d_o is not None else None, lse_b if d_o is not None else None)
+    out = {"o": o, "lse": lse, "plan": plan, "partial_batch": pb, "n_parts": int(part_rows.shape[0])}
+    if d_o is not None:
+        dop = d_o.index_select(0, g).contiguous()
+        dq_p = torch.full_like(qp, float("nan"))
+        dk = torch.full_like(k, float("nan"))
+        dv = torch.full_like(v, float("nan"))
+        B.ca_backward(plan, qp, k, v, o_b, dop, lse_b, dq_p, dk, dv, ws)
+        dq = torch.full_like(q, float("nan"))
+        B.ca_sum_partial_dq(pr, dq_p, dq)
+        out.update(dq=dq, dk=dk, dv=dv, o_back=o_b, lse_back=lse_b)
+    torch.cuda.synchronize()
+    return out
+
+
 def run_oracle(batch, q, k, v, d_o=None, want=("dq", "dk", "dv")):
     q64, k64, v64 = to64(q), to64(k), to64(v)
     if d_o is None:

@@ -19,7 +19,8 @@ def test_header_functions_are_exported():
     names = declared_functions()
     assert {"ca_plan", "ca_plan_host", "ca_plan_upload", "ca_forward", "ca_backward", "ca_plan_destroy",
             "ca_plan_workspace_bytes", "ca_error_string", "ca_last_error", "ca_profile_enable",
-            "ca_profile_read", "ca_plan_info", "ca_plan_rows", "ca_plan_fwd_units", "ca_plan_bwd_units"} <= set(names)
+            "ca_profile_read", "ca_plan_info", "ca_plan_rows", "ca_plan_fwd_units", "ca_plan_bwd_units",
+            "ca_merge_partials", "ca_sum_partial_dq"} <= set(names)
     lib = ctypes.CDLL(B.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -41,3 +42,18 @@ def test_calls_without_plan_fail_cleanly():
     assert lib.ca_plan_workspace_bytes(None, None, None) == B.CA_ERR_INVALID_ARG
     assert lib.ca_plan_host(None, None) == B.CA_ERR_INVALID_ARG
     lib.ca_plan_destroy(None)  # no-op
+
+
+def test_merge_entry_points_reject_bad_arguments_on_the_host():
+    lib = B.lib()
+    # counts and head_dim are checked before anything touches a device
+    assert lib.ca_merge_partials(None, 4, 0, None, None, 4, None, None, None, None, 2, 64, None) == B.CA_ERR_INVALID_ARG
+    assert b"n_parts" in lib.ca_last_error()
+    assert lib.ca_merge_partials(None, 4, 65, None, None, 4, None, None, None, None, 2, 64, None) == B.CA_ERR_INVALID_ARG
+    assert lib.ca_merge_partials(None, 4, 2, None, None, 4, None, None, None, None, 2, 96, None) == B.CA_ERR_UNSUPPORTED
+    assert lib.ca_merge_partials(None, 4, 2, None, None, 4, None, None, None, None, 2, 64, None) == B.CA_ERR_INVALID_ARG
+    assert b"null" in lib.ca_last_error()
+    assert lib.ca_sum_partial_dq(None, -1, 2, None, 4, None, 2, 64, None) == B.CA_ERR_INVALID_ARG
+    assert lib.ca_sum_partial_dq(None, 4, 2, None, 4, None, 2, 64, None) == B.CA_ERR_INVALID_ARG
+    # nothing to do: no launch, no error
+    assert lib.ca_merge_partials(None, 0, 1, None, None, 0, None, None, None, None, 2, 64, None) == B.CA_OK

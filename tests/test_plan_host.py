@@ -45,7 +45,7 @@ def test_valid_descriptor_plans():
     ("q out of range", dict(task_q_start=lambda a: a.__setitem__(1, 10**6)), B.CA_ERR_INVALID_ARG, "outside packed Q"),
     ("q overlap", dict(task_q_start=lambda a: a.__setitem__(1, int(a[0]) + 1)), B.CA_ERR_INVALID_ARG, "overlap"),
     ("negative pos", dict(task_q_pos=lambda a: a.__setitem__(0, -1)), B.CA_ERR_INVALID_ARG, "q_pos"),
-    ("row cannot see itself", dict(task_kv_len=lambda a: a.__setitem__(1, 39)), B.CA_ERR_INVALID_ARG, "see itself"),
+    ("task without keys", dict(task_kv_len=lambda a: a.__setitem__(1, 0)), B.CA_ERR_INVALID_ARG, "at least one key"),
     ("kv_len beyond doc", dict(task_kv_len=lambda a: a.__setitem__(1, 41)), B.CA_ERR_INVALID_ARG, "resident KV"),
     ("doc out of buffer", dict(doc_kv_start=lambda a: a.__setitem__(1, 10**6)), B.CA_ERR_INVALID_ARG, "outside the packed KV"),
     ("doc overlap", dict(doc_kv_start=lambda a: a.__setitem__(0, int(a[2]))), B.CA_ERR_INVALID_ARG, "overlap"),
@@ -91,7 +91,7 @@ def check_schedule(b):
     want_doc = np.full(b.total_q, -1, np.int64)
     for t in range(b.n_tasks):
         sl = slice(int(b.task_q_start[t]), int(b.task_q_start[t] + b.task_q_len[t]))
-        want_pos[sl] = b.task_q_pos[t] + np.arange(b.task_q_len[t])
+        want_pos[sl] = np.minimum(b.task_q_pos[t] + np.arange(b.task_q_len[t]), b.task_kv_len[t] - 1)  # last key seen
         want_doc[sl] = b.task_doc[t]
     real = rows >= 0
     assert sorted(rows[real].tolist()) == np.flatnonzero(want_pos >= 0).tolist()
@@ -165,6 +165,23 @@ def test_schedule_invariants_small_and_ragged():
         b = W.custom([40, 300, 1000, 257], [(0, 0, 40), (1, 0, 300), (2, 100, 333), (2, 600, 400), (3, 0, 257)], hq, hkv, 64)
         info = check_schedule(b).info()
         assert info["heads_packed"] == {8: 8, 4: 4, 2: 2, 1: 1, 3: 1}[hq // hkv]
+
+
+def test_schedule_invariants_of_key_window_tasks():
+    """Tasks clipped to a key window (kv_len < q_pos + q_len): their slots carry the last key they see."""
+    b = W.custom([700], [(0, 100, 300)], 4, 2, 64)
+    b.task_kv_len[0] = 250  # rows at positions 250..399 all see keys 0..249
+    p = check_schedule(b)
+    _, pos = p.rows()
+    assert pos[:300].tolist() == list(range(100, 250)) + [249] * 150
+    # a later task clipped below an earlier one: slots are re-sorted by the last key seen
+    b = W.custom([700], [(0, 0, 200), (0, 200, 100)], 4, 2, 64)
+    b.task_kv_len[1] = 50
+    check_schedule(b)
+    for window in (64, 100, 333):
+        pb, gather, part_rows = W.split_kv(W.config(1), window)
+        check_schedule(pb)
+        assert pb.pairs() == W.config(1).pairs()
 
 
 @pytest.mark.parametrize("idx", [2, 3, 4, 5])
