@@ -1,0 +1,58 @@
+"""The forward and backward calls allocate nothing and never synchronise, so a caller can record them into a HIP
+graph once and replay it (Section 6.2 reports allocator and launch overhead from the varying shapes of
+CA-tasks and names static allocation plus graphs as the remedy).  Replays are checked against the eager result bit
+for bit, with eager work and synchronisations between them."""
+import pytest
+import torch
+
+from paper_2510_18121_amd import binding as B
+from paper_2510_18121_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def test_forward_backward_and_merge_replay_from_a_graph():
+    b = W.one_kv_group(W.config(3, 32))
+    pb, gather, part_rows = W.split_kv(b, 512)
+    q, k, v, d_o = W.make_tensors(b, DEV)
+    g = torch.as_tensor(gather, device=DEV)
+    pr = torch.as_tensor(part_rows, device=DEV).contiguous()
+    qp, dop = q.index_select(0, g).contiguous(), d_o.index_select(0, g).contiguous()
+    plan = B.ca_plan(pb)
+    ws = B.alloc_workspace(plan, DEV)
+    o_p, dq_p = torch.empty_like(qp), torch.empty_like(qp)
+    lse_p = torch.empty((pb.n_q_heads, pb.total_q), dtype=torch.float32, device=DEV)
+    o, dq = torch.empty_like(q), torch.empty_like(q)
+    lse = torch.empty((b.n_q_heads, b.total_q), dtype=torch.float32, device=DEV)
+    dk, dv = torch.empty_like(k), torch.empty_like(v)
+    outs = (o, lse, dq, dk, dv)
+
+    def step():
+        B.ca_forward(plan, qp, k, v, o_p, lse_p, ws)
+        B.ca_merge_partials(pr, o_p, lse_p, o, lse, o_p, lse_p)
+        B.ca_backward(plan, qp, k, v, o_p, dop, lse_p, dq_p, dk, dv, ws)
+        B.ca_sum_partial_dq(pr, dq_p, dq)
+
+    step()  # eager: also the first-call set-up of the kernels (dynamic LDS size attribute)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in outs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        for t in outs + (o_p, lse_p, dq_p):
+            t.fill_(float("nan"))  # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for t, w in zip(outs, want):
+            assert torch.equal(t, w), f"replay {rep} differs from the eager result"
+        # new inputs in the same buffers: the graph computes on what the buffers hold at replay time
+    qp.mul_(0.5)
+    graph.replay()
+    torch.cuda.synchronize()
+    got = o.clone()
+    step()
+    torch.cuda.synchronize()
+    assert torch.equal(got, o)
