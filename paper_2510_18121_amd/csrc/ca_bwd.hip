@@ -4,8 +4,8 @@
 //   prep : per (slot, head): -Delta = -<dO, O> and L2 = log2(e) * LSE, stored in SLOT order (the order of the
 //          planner's per-document sorted query rows), so that both main kernels read them contiguously.
 //          Padding slots get L2 = +huge, which makes their recomputed probabilities exactly 0.
-//   dq   : one workgroup = 256 query slots x one query head (the forward's work units), walking over the
-//          document's keys like the forward does.  Lane <-> query row:
+//   dq   : one workgroup = one of the forward's work units (256 query slots x one query head, or 256/hp slots x hp
+//          heads of one KV group), walking over the document's keys like the forward does.  Lane <-> query row:
 //            S^T = K Q^T, dP^T = V dO^T, P^T = exp2(c S^T - L2), dS^T = P^T (dP^T - Delta),
 //            dQ^T += K^T dS^T   (K^T through transposing LDS reads of the same K tile)
 //   dkv  : one workgroup = 128 keys of one document x one KV head, walking over every block of 64 query

@@ -1,8 +1,10 @@
 // Forward kernel: O = softmax(scale * Q K^T, causal) V and LSE over tiles of query rows
 // (core attention, Section 2.1; one fused launch over all CA-tasks, Section 4.1).
 //
-// One workgroup = one forward unit = 256 query slots of one document x one query head; 8 waves of
-// 32 slots, two per SIMD, one workgroup per CU.  The wave computes the TRANSPOSED score block S^T = K Q^T
+// One workgroup = one forward unit = 256 query slots of one document x one query head, or, for the slots a
+// document has left over after its full tiles, 256/hp slots x hp query heads of one KV group (same K/V tiles,
+// same loads; only the wave -> (slot group, head) mapping differs); 8 waves of 32 slots, two per SIMD, one
+// workgroup per CU.  The wave computes the TRANSPOSED score block S^T = K Q^T
 // with v_mfma_f32_32x32x16_bf16, so that a lane owns one query row (column l%32 of the MFMA result) and its
 // 16 registers per block are 16 different keys: row max and row sum are in-lane work plus one exchange
 // between lanes l and l+32.  The bf16 probabilities, still in those registers, are exactly the B operand of
@@ -15,8 +17,8 @@
 // issues the MFMAs of the next block's scores, the exponentials of this block, the MFMAs of this block's P V
 // and the row maximum of the next block, so that the vector work sits in the instruction stream between
 // independent matrix instructions.  That straight-line form is used for tiles entirely below the diagonal of
-// the wave's rows; diagonal tiles take a general path with masking.  The softmax runs in base 2 with scale*log2(e) folded into one FMA and rescales
-// the accumulators lazily.
+// the wave's rows; diagonal tiles take a general path with masking.  The softmax runs in base 2 with
+// scale*log2(e) folded into one FMA and rescales the accumulators lazily.
 #include <type_traits>
 
 #include "ca_device.h"
@@ -224,25 +226,6 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     barrier_nofence();  // ... and everybody else's; everybody is done with K(j-1) and V(j-1)
     issue_kv(kg, S::K_OFF, j + 3);
     issue_kv(vg, S::V_OFF, j + 3);
-  };
-
-  // Instruction order of one pipeline step (a hint to the scheduler; the hardware issues a wave's instructions
-  // in order, so vector work only overlaps matrix work that surrounds it in the stream): the 8 K-fragment reads,
-  // then every score MFMA followed by a share of the exponentials, then every P V MFMA preceded by its two
-  // transposing reads and followed by a share of the row maximum.
-  auto interleave = [&]() __attribute__((always_inline)) {
-    __builtin_amdgcn_sched_group_barrier(0x100, NS, 0);  // DS reads
-#pragma unroll
-    for (int i = 0; i < NS; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-      __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);  // VALU
-    }
-#pragma unroll
-    for (int i = 0; i < 2 * NDB; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
-    }
   };
 
   // Tile j and block 0 of tile j+1 fully visible: no mask, no skip.  After each (rare) rescale there is one
