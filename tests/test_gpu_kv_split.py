@@ -55,6 +55,20 @@ def test_ragged_windows_and_head_layouts():
         check(b, window, f"ragged d{d} {hq}/{hkv} window {window}")
 
 
+def test_one_key_windows_and_the_part_limit():
+    """Windows of a single key (every partial task sees exactly one key: its softmax is 1 and all the weighting
+    happens in the merge), up to the limit of 64 parts per row; one part more is refused."""
+    b = W.custom([40, 64], [(0, 0, 40), (1, 10, 54)], 4, 2, 64, seed=35)
+    hip, _ = check(b, 1, "one-key windows")
+    assert hip["n_parts"] == 64
+    pr = torch.zeros((65, 8), dtype=torch.int32, device=DEV)
+    o_part = torch.zeros((8, 4, 64), dtype=torch.bfloat16, device=DEV)
+    lse_part = torch.zeros((4, 8), device=DEV)
+    with pytest.raises(B.CaError) as e:
+        B.ca_merge_partials(pr, o_part, lse_part, torch.empty_like(o_part), torch.empty_like(lse_part))
+    assert e.value.code == B.CA_ERR_INVALID_ARG and "n_parts" in e.value.detail
+
+
 def test_clipped_task_without_merge():
     """A single task whose kv_len stops short of its rows: the HIP path against the oracle of that very task."""
     b = W.custom([900], [(0, 100, 600)], 4, 2, 128, seed=32)
