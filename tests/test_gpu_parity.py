@@ -180,3 +180,18 @@ def test_profile_hook_reports_kernel_times():
     t = plan.profile_read()
     assert t["fwd_kernel_ms"] > 0 and t["bwd_dkv_ms"] > 0 and t["bwd_dq_ms"] > 0
     plan.profile_enable(False)
+
+
+def test_autograd_wrapper_matches_the_direct_calls():
+    """The differentiable op is the two C-ABI calls: same bits as calling them directly."""
+    from paper_2510_18121_amd.autograd import AttentionServer
+    b = W.config(1)
+    q, k, v, d_o = W.make_tensors(b, DEV)
+    direct = P.run_hip(b, q, k, v, d_o)
+    qa, ka, va = (t.clone().requires_grad_(True) for t in (q, k, v))
+    server = AttentionServer(b, DEV)
+    o = server(qa, ka, va)
+    o.backward(d_o)
+    torch.cuda.synchronize()
+    assert torch.equal(o.detach(), direct["o"])
+    assert torch.equal(qa.grad, direct["dq"]) and torch.equal(ka.grad, direct["dk"]) and torch.equal(va.grad, direct["dv"])
