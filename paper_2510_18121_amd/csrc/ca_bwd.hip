@@ -487,24 +487,18 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
         for (int e = 0; e < 4; ++e) ndt[4 * i4 + e] = x[e];
       }
     };
-    // P of query row 4 i4 + e of this lane's 16 (e = 0..3), and after every second one the packed pair.
-    // The empty volatile asm on one input of each piece of vector work keeps the instruction selector from hoisting
-    // the (side-effect-free) arithmetic across the sched_barrier fences of earlier MFMA slots: the work of a slot
-    // stays in its slot.
+    // P of query row 4 i4 + e of this lane's 16 (e = 0..3).  The vector work is written as volatile asm statements
+    // (exp2_fma_pinned and friends): they stay in the MFMA slot they are written in, which plain arithmetic would not
+    // (the instruction selector hoists side-effect-free code across the sched_barrier fences of earlier slots).  A
+    // pair of probabilities is packed to bf16 one slot after its second exponential, so that no wait state is
+    // needed between the transcendental and the conversion that reads it.
     auto vec_p1 = [&](const f32x16 &sa, int i4, int e) __attribute__((always_inline)) {
-      float g = l2v[i4][e];
-      pin(g);
-      pv[4 * i4 + e] = fast_exp2(fmaf(sa[4 * i4 + e], c, -g));
-      if (e & 1) pw[2 * i4 + (e >> 1)] = pack_bf16(pv[4 * i4 + e - 1], pv[4 * i4 + e]);
+      pv[4 * i4 + e] = exp2_fma_pinned(sa[4 * i4 + e], c, l2v[i4][e]);
     };
-    auto vec_p = [&](const f32x16 &sa, int i4, int h) __attribute__((always_inline)) {
-      vec_p1(sa, i4, 2 * h);
-      vec_p1(sa, i4, 2 * h + 1);
-    };
+    auto pack_p = [&](int k) __attribute__((always_inline)) { pw[k] = pack_bf16_pinned(pv[2 * k], pv[2 * k + 1]); };
     auto vec_ds = [&](const f32x16 &da, int i4) __attribute__((always_inline)) {
-      pin(pv[4 * i4]);
-      dw[2 * i4] = pack_bf16(pv[4 * i4] * da[4 * i4], pv[4 * i4 + 1] * da[4 * i4 + 1]);
-      dw[2 * i4 + 1] = pack_bf16(pv[4 * i4 + 2] * da[4 * i4 + 2], pv[4 * i4 + 3] * da[4 * i4 + 3]);
+      mul_pack_bf16_pinned(pv[4 * i4], pv[4 * i4 + 1], pv[4 * i4 + 2], pv[4 * i4 + 3], da[4 * i4], da[4 * i4 + 1],
+                           da[4 * i4 + 2], da[4 * i4 + 3], dw[2 * i4], dw[2 * i4 + 1]);
     };
     // Score chain of one sub-block into (sw, dpw); nat = offset of its natural tiles from qoff's stage.  With VEC,
     // P of the first 12 of the lane's 16 rows of (sr) is formed between the MFMAs (the rest follows in phase B: the
@@ -523,10 +517,12 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
         if (s + PA < NS) opq[s % PA] = lds_read8_at(S::Q_OFF + nat + qoff[s + PA]);
         if (vec) {
           tlo = lds_read_tr4_at(X + toff[0][s >> 1]);
-          if constexpr (NS == 8) {
+          if constexpr (NS == 8) {  // pair s in step s (one exponential per MFMA), packed in step s + 1
+            if (s >= 1 && s < 7) pack_p(s - 1);
             if (s < 6) vec_p1(sr, s >> 1, 2 * (s & 1));
-          } else {
-            if (s < 3) vec_p(sr, s, 0);
+          } else {  // pairs 2s and 2s+1 in step s (two exponentials per MFMA), each packed one MFMA later
+            if (s >= 1) pack_p(2 * s - 1);
+            if (s < 3) vec_p1(sr, s, 0), vec_p1(sr, s, 1);
           }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -539,7 +535,7 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
           if constexpr (NS == 8) {
             if (s < 6) vec_p1(sr, s >> 1, 2 * (s & 1) + 1);
           } else {
-            if (s < 3) vec_p(sr, s, 1);
+            if (s < 3) pack_p(2 * s), vec_p1(sr, s, 2), vec_p1(sr, s, 3);
           }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -608,13 +604,16 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
               if constexpr (NDB == 4) {
                 if (m == 0) vec_ds(dp[qb], 0);
                 if (m == 1) vec_ds(dp[qb], 1);
-                if (m == 2) vec_p(sc[qb], 3, 0);
-                if (m == 3) vec_p(sc[qb], 3, 1);
+                if (m == 2) vec_p1(sc[qb], 3, 0), vec_p1(sc[qb], 3, 1);
+                if (m == 3) vec_p1(sc[qb], 3, 2), vec_p1(sc[qb], 3, 3), pack_p(6);  // a pack never directly follows
+                if (m == 4) pack_p(7);                                              // the exponentials it reads
                 if (m == 8) vec_ds(dp[qb], 2);
                 if (m == 9) vec_ds(dp[qb], 3);
               } else {
                 if (m == 0) vec_ds(dp[qb], 0), vec_ds(dp[qb], 1);
-                if (m == 1) vec_p(sc[qb], 3, 0), vec_p(sc[qb], 3, 1);
+                if (m == 1) vec_p1(sc[qb], 3, 0), vec_p1(sc[qb], 3, 1);
+                if (m == 2) vec_p1(sc[qb], 3, 2), vec_p1(sc[qb], 3, 3), pack_p(6);
+                if (m == 3) pack_p(7);
                 if (m == 4) vec_ds(dp[qb], 2), vec_ds(dp[qb], 3);
               }
               // first natural fragments of sub-block k+2 (block it+1: first half for qb == 0, second for qb == 1)

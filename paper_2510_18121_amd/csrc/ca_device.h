@@ -207,6 +207,29 @@ __device__ __forceinline__ void mfma_settle(f32x16 &x, f32x16 &y, const f32x16 &
   asm volatile("s_nop 11" : "+v"(x), "+v"(y) : "v"(c));
 }
 __device__ __forceinline__ void pin(float &v) { asm volatile("" : "+v"(v)); }
+// exp2(x * c - g) as one volatile asm statement: like pin() it stays where it is written in the instruction stream
+// (between the MFMAs of its slot), but without the wait state the compiler puts between an empty asm that "defines"
+// a register and the first instruction that reads it.  (A multiply-add feeding a transcendental needs no wait state.)
+__device__ __forceinline__ uint32_t pack_bf16_pinned(float a, float b) {
+  uint32_t r;
+  asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+// {bf16(p0 * d0), bf16(p1 * d1)} and {bf16(p2 * d2), bf16(p3 * d3)}, pinned likewise
+__device__ __forceinline__ void mul_pack_bf16_pinned(float p0, float p1, float p2, float p3, float d0, float d1,
+                                                     float d2, float d3, uint32_t &lo, uint32_t &hi) {
+  float t0, t1, t2, t3;
+  asm volatile(
+      "v_mul_f32 %2, %6, %10\n\tv_mul_f32 %3, %7, %11\n\tv_mul_f32 %4, %8, %12\n\tv_mul_f32 %5, %9, %13\n\t"
+      "v_cvt_pk_bf16_f32 %0, %2, %3\n\tv_cvt_pk_bf16_f32 %1, %4, %5"
+      : "=&v"(lo), "=&v"(hi), "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3)
+      : "v"(p0), "v"(p1), "v"(p2), "v"(p3), "v"(d0), "v"(d1), "v"(d2), "v"(d3));
+}
+__device__ __forceinline__ float exp2_fma_pinned(float x, float c, float g) {
+  float r;
+  asm volatile("v_fma_f32 %0, %1, %2, -%3\n\tv_exp_f32 %0, %0" : "=v"(r) : "v"(x), "v"(c), "v"(g));
+  return r;
+}
 __device__ __forceinline__ void pin(int &v) { asm volatile("" : "+v"(v)); }
 
 // wait until at most n of this wave's vector-memory loads are outstanding (n <= 63)
