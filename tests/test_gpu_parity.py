@@ -195,3 +195,38 @@ def test_autograd_wrapper_matches_the_direct_calls():
     torch.cuda.synchronize()
     assert torch.equal(o.detach(), direct["o"])
     assert torch.equal(qa.grad, direct["dq"]) and torch.equal(ka.grad, direct["dk"]) and torch.equal(va.grad, direct["dv"])
+
+
+def _random_batch(seed):
+    """A seeded random small batch: 1-5 documents of 1-700 tokens, each cut into 0-4 ragged shards (gaps allowed,
+    some shards clipped to a shorter key prefix), random head layout and head_dim, shuffled packing orders."""
+    rng = np.random.default_rng(9000 + seed)
+    hkv = int(rng.choice([1, 2, 3]))
+    g = int(rng.choice([1, 2, 3, 4, 8]))
+    d = int(rng.choice([64, 128]))
+    n_docs = int(rng.integers(1, 6))
+    docs = [int(rng.integers(1, 701)) for _ in range(n_docs)]
+    tasks = []
+    for dd, n in enumerate(docs):
+        cuts = sorted(set(int(x) for x in rng.integers(0, n + 1, size=int(rng.integers(0, 6)))))
+        for a, e in zip(cuts[:-1], cuts[1:]):
+            if e > a and rng.random() < 0.8:  # 20 % of the pieces are left out: gaps
+                tasks.append((dd, a, e - a))
+    b = W.custom(docs, tasks, hkv * g, hkv, d, doc_order=[int(x) for x in rng.permutation(n_docs)],
+                 task_order=[int(x) for x in rng.permutation(len(tasks))], seed=100 + seed)
+    for t in range(b.n_tasks):
+        if rng.random() < 0.25:  # clip to a key window shorter than the causal prefix
+            b.task_kv_len[t] = int(rng.integers(1, b.task_kv_len[t] + 1))
+    return b
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_small_batches(seed):
+    b = _random_batch(seed)
+    tag = f"random {seed}: {b.n_docs} docs, {b.n_tasks} tasks, {b.n_q_heads}/{b.n_kv_heads} heads, d {b.head_dim}"
+    if b.n_tasks == 0:
+        q, k, v, d_o = W.make_tensors(b, DEV)
+        hip = P.run_hip(b, q, k, v, d_o)
+        assert torch.all(hip["dk"] == 0) and torch.all(hip["dv"] == 0)
+        return
+    full_check(b, tag)
