@@ -103,7 +103,7 @@ def test_merge_kernel_against_the_oracle_merge_with_missing_parts():
     o_ref, lse_ref = oracle.merge_partials(perm, P.to64(o_part), lse_part.double().cpu().numpy())
     assert P.o_errors(P.to64(o), o_ref)[1] <= 1.0  # 1e-2, or one bf16 rounding where |O| >= 4 (inputs are N(0,1) here)
     has = (perm >= 0).any(axis=0)
-    assert np.abs(lse.double().cpu().numpy() - lse_ref)[:, has].max() <= 1e-5 * 10
+    assert np.abs(lse.double().cpu().numpy()[:, has] - lse_ref[:, has]).max() <= 1e-4
     assert torch.all(o[:7] == 0) and torch.all(torch.isneginf(lse[:, :7]))
     sum_ref = np.zeros((n_rows, hq, d))
     o64 = P.to64(o_part)
