@@ -106,8 +106,10 @@ int ca_forward(const ca_plan_t *plan, const void *q, const void *k, const void *
  * (nothing else is kept between the two calls).  dq like q; dk, dv like k, v (every row written).
  * ws: device workspace of at least bwd_bytes, 256-byte aligned.  It receives, for every (query head, padded row
  * slot), fp32 -<dO, O> and log2(e)*LSE, and position-sorted bf16 copies of Q and dO
- * (bwd_bytes is about 2 * n_q_heads * padded_rows * (4 + 2 * head_dim) bytes: a little over the size of Q plus dO).
- * No atomics are used: results are bit-reproducible from run to run.  Allocates nothing, never synchronises.
+ * (bwd_bytes is about 2 * n_q_heads * padded_rows * (4 + 2 * head_dim) bytes: a little over the size of Q plus dO),
+ * and one 4-byte progress counter per backward work unit, through which workgroups that read the same Q/dO tiles pace
+ * each other (timing only).  No arithmetic uses atomics: results are bit-reproducible from run to run.  Allocates
+ * nothing, never synchronises.
  */
 int ca_backward(const ca_plan_t *plan, const void *q, const void *k, const void *v, const void *o,
                 const void *d_o, const float *lse, void *dq, void *dk, void *dv,

@@ -29,13 +29,15 @@ __global__ void ca_bwd_prep_kernel(const int32_t *__restrict__ slot_row, const b
                                    const bf16_t *__restrict__ O, const bf16_t *__restrict__ dO,
                                    const float *__restrict__ LSE, float *__restrict__ delta_slot,
                                    float *__restrict__ l2_slot, bf16_t *__restrict__ q_sorted,
-                                   bf16_t *__restrict__ do_sorted, int64_t padded, int64_t total_q, int Hq, int D) {
+                                   bf16_t *__restrict__ do_sorted, int32_t *__restrict__ progress, int n_progress,
+                                   int64_t padded, int64_t total_q, int Hq, int D) {
   // D/8 lanes per (slot, head): -Delta = -<dO, O> and log2(e)*LSE in slot order, and the slot-ordered copies of
   // Q and dO as [block of 64 slots][head][64][D]: the 64-slot tile of a (block, head) is one contiguous run, and
   // the tiles of the heads of a block follow each other (padding slots: zeros, with an LSE that makes every
   // probability 0)
   const int lanes = D / 8;
   const int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (idx < n_progress) progress[idx] = 0;  // progress counters of the dK/dV workgroups: nobody has started
   const int64_t pair = idx / lanes;
   const int c = int(idx % lanes);
   const bool ok = pair < padded * Hq;
@@ -285,8 +287,9 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
                                                             const bf16_t *__restrict__ V, const bf16_t *__restrict__ dOs,
                                                             const float *__restrict__ l2_slot,
                                                             const float *__restrict__ delta_slot,
-                                                            bf16_t *__restrict__ dK, bf16_t *__restrict__ dV, int Hq,
-                                                            int Hkv, int64_t padded, float scale) {
+                                                            bf16_t *__restrict__ dK, bf16_t *__restrict__ dV,
+                                                            int32_t *progress, int peer_stride, int Hq, int Hkv,
+                                                            int64_t padded, float scale) {
   using S = DkvSmem<D>;
   constexpr int NS = D / 16, NDB = D / 32, CH = D / 8, RPI = 64 / CH, NST = S::NST;
   constexpr int NLD = BWD_BQ / (4 * RPI);  // direct loads per wave per Q (or dO) tile
@@ -335,10 +338,36 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   // the wave's auxiliary array: log2e*LSE (wave 0), -Delta (wave 1), slot positions (wave 2; wave 3 repeats them
   // into a spare area so that every wave issues the same number of loads)
   const int64_t aux_hstride = wave < 2 ? padded : 0;
+  const int aux_bstep = wave == 3 ? 0 : BWD_BQ;
   const float *aux_ptr = (wave == 0 ? l2_slot + int64_t(hk) * G * padded
                           : wave == 1 ? delta_slot + int64_t(hk) * G * padded
                                       : reinterpret_cast<const float *>(slot_pos)) +
                          u.slot_begin + int64_t(pblk) * BWD_BQ + lane;
+  // Convoy.  The workgroups of one KV head that run on one XCD (units peer_stride apart) walk the same Q/dO tiles
+  // from the same last block; as long as they are within an L2's worth of steps of each other only the first
+  // of them fetches a tile from beyond the L2.  Each workgroup publishes the number of steps it has taken; wave 3's
+  // auxiliary load (a filler otherwise) fetches the counters of up to 32 such peers along with every stage, and a
+  // workgroup that finds a peer between CONVOY and CONVOY_REACH steps behind sleeps about 4 microseconds per step
+  // until the peer has caught up (peers further behind are left alone; the slowest workgroup never sleeps, so nothing
+  // can dead-lock, and results do not depend on any of this).  Counters are published every eighth step: a store per
+  // step would sit in the wave's memory queue ahead of the loads its s_waitcnt bookkeeping waits for.
+  constexpr int CONVOY = (1 << 20) / (2 * BWD_BQ * ROWB);  // 1 MB of Q/dO tiles (a quarter of an L2), in steps
+  constexpr int CONVOY_REACH = 3 * CONVOY;                 // peers further behind than this are left alone
+  const int n_units = int(gridDim.x);
+  if (wave == 3) {
+    const int me = int(blockIdx.x), grp = 32 * peer_stride;
+    const int pu = me - me % grp + me % peer_stride + peer_stride * lane;
+    const int32_t *pp = progress + n_units;  // a counter that stays 0: "not running"
+    if (lane < 32 && pu < n_units && pu != me) {
+      const BwdUnit o = units[pu];
+      if (o.slot_end == u.slot_end && o.kv_head == u.kv_head && o.slot_end > o.slot_begin) pp = progress + pu;
+    }
+    aux_ptr = reinterpret_cast<const float *>(pp);
+  }
+  int32_t *const my_progress = progress + blockIdx.x;
+  auto publish = [&](int steps) __attribute__((always_inline)) {  // call from wave 3 only
+    if (lane == 0) __hip_atomic_store(my_progress, steps, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  };
   const uint32_t aux_lds = wave == 0 ? S::L2_OFF : wave == 1 ? S::DL_OFF : wave == 2 ? S::POS_OFF : S::SPARE_OFF;
   constexpr int LPI = 2 * NLD + 1;  // loads per wave per iteration
   // The loads of one (block, head) come in LPI pieces, so that the pipelined path can hand them to the memory
@@ -351,7 +380,7 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
                        pst_addr + ((i & 1) ? S::DO_OFF : S::Q_OFF) + (RPW * wave + RPI * n) * ROWB);
       return;
     }
-    load_lds4_at(aux_ptr, pst_addr + aux_lds);
+    load_lds4_at_fresh(aux_ptr, pst_addr + aux_lds);  // device scope for all four waves: no branch; the others' arrays are read once anyway
     pst = pst + 1 == NST ? 0 : pst + 1;
     pst_addr = pst == 0 ? lds0 : pst_addr + S::STAGE;
     if (ph + 1 < G) {  // next head of the group, same block
@@ -361,7 +390,7 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
       ph = 0;
       --pblk;
       q_tile -= (G - 1) * head_stride + block_stride, do_tile -= (G - 1) * head_stride + block_stride;
-      aux_ptr -= (G - 1) * aux_hstride + BWD_BQ;
+      aux_ptr -= (G - 1) * aux_hstride + aux_bstep;
     }  // else: past the end, keep re-fetching the final (block, head)
   };
   auto issue_next = [&]() __attribute__((always_inline)) {
@@ -562,6 +591,8 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
     load_nd(auxq + 32 * 4);
 
     for (; it < n_fast; ++it) {
+      // wave 3: a peer's counter as of about three steps ago (the other waves read their own filler)
+      const int peer_steps = lds_ld<int>(auxo - 16 * g + S::SPARE_OFF + 4 * lane);
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
         // ---- phase A: scores of the next sub-block (the other half of this block, or the first half of the
@@ -636,6 +667,11 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
           }
         }
       }
+      if (wave == 3) {
+        if ((it & 7) == 7) publish(it + 1);
+        const int lead = it + 1 - peer_steps;
+        if (__any(peer_steps > 0 && lead > CONVOY && lead <= CONVOY_REACH)) __builtin_amdgcn_s_sleep(127);
+      }
     }
   }
 
@@ -707,7 +743,9 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
     issue_next();       // block it+4 into it
     advance_q();
     advance_t();
+    if (wave == 3) publish(it + 1);
   }
+  if (wave == 3) publish(-1);  // finished: peers no longer wait for this workgroup
   wait_vmcnt<0>();  // nothing may still be writing LDS when the workgroup ends
 
   // ---- write dK (scaled) and dV of the wave's 32 keys
@@ -756,6 +794,7 @@ static hipError_t launch_bwd_t(const ca_plan_t *p, const void *q, const void *k,
   float *l2_slot = reinterpret_cast<float *>(static_cast<char *>(ws) + p->ws_off_l2);
   bf16_t *q_sorted = reinterpret_cast<bf16_t *>(static_cast<char *>(ws) + p->ws_off_qs);
   bf16_t *do_sorted = reinterpret_cast<bf16_t *>(static_cast<char *>(ws) + p->ws_off_dos);
+  int32_t *progress = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + p->ws_off_prog);
   // rows that belong to no work unit (KV outside every scheduled document, Q rows outside every task)
   if (!p->kv_covered) {
     launch_fill(dk, kv_elems * 2, st);
@@ -763,10 +802,11 @@ static hipError_t launch_bwd_t(const ca_plan_t *p, const void *q, const void *k,
   }
   if (!p->q_covered) launch_fill(dq, q_elems * 2, st);
   if (padded > 0) {
-    const int64_t threads = padded * p->hq * (D / 8);
+    const int n_progress = int(p->bwd_units.size()) + 64;
+    const int64_t threads = std::max<int64_t>(padded * p->hq * (D / 8), n_progress);
     hipLaunchKernelGGL(ca_bwd_prep_kernel, dim3(unsigned((threads + 255) / 256)), dim3(256), 0, st, p->d_slot_row,
                        static_cast<const bf16_t *>(q), static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(d_o),
-                       lse, delta_slot, l2_slot, q_sorted, do_sorted, padded, p->total_q, p->hq, D);
+                       lse, delta_slot, l2_slot, q_sorted, do_sorted, progress, n_progress, padded, p->total_q, p->hq, D);
   }
   if (ev) (void)hipEventRecord(ev[1], st);
   if (!p->bwd_units.empty()) {
@@ -777,7 +817,8 @@ static hipError_t launch_bwd_t(const ca_plan_t *p, const void *q, const void *k,
     hipLaunchKernelGGL(kern, dim3(unsigned(p->bwd_units.size())), dim3(256), DkvSmem<D>::TOTAL, st, p->d_bwd_units,
                        p->d_slot_pos, q_sorted, static_cast<const bf16_t *>(k), static_cast<const bf16_t *>(v),
                        do_sorted, l2_slot, delta_slot,
-                       static_cast<bf16_t *>(dk), static_cast<bf16_t *>(dv), p->hq, p->hkv, padded, p->scale);
+                       static_cast<bf16_t *>(dk), static_cast<bf16_t *>(dv), progress, p->peer_stride, p->hq, p->hkv,
+                       padded, p->scale);
   }
   if (ev) (void)hipEventRecord(ev[2], st);
   if (!p->fwd_units.empty()) {

@@ -144,6 +144,13 @@ __device__ __forceinline__ void load_lds4_at(const void *src, uint32_t lds_addr_
                : "v"(src), "s"(lds_addr_uniform)
                : "memory", "m0");
 }
+// the same, read at device scope (past this CU's vector L1): for values other workgroups keep writing
+__device__ __forceinline__ void load_lds4_at_fresh(const void *src, uint32_t lds_addr_uniform) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off sc1"
+               :
+               : "v"(src), "s"(lds_addr_uniform)
+               : "memory", "m0");
+}
 __device__ __forceinline__ void load_lds4(const void *src, char *lds_base_uniform) {
   const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(CA_LDS char *)lds_base_uniform);
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"

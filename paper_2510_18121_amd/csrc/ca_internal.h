@@ -55,7 +55,8 @@ struct ca_plan {
   int64_t fwd_steps = 0, bwd_steps = 0;
   // workspace layout for backward: [Delta fp32 hq*padded_slots][log2e*LSE fp32 hq*padded_slots]
   int slot_align = ca::SLOT_ALIGN, heads_packed = 1;  // padding of a document's slots; hp of the packed units
-  size_t ws_fwd = 0, ws_bwd = 0, ws_off_l2 = 0, ws_off_qs = 0, ws_off_dos = 0;
+  size_t ws_fwd = 0, ws_bwd = 0, ws_off_l2 = 0, ws_off_qs = 0, ws_off_dos = 0, ws_off_prog = 0;
+  int peer_stride = 8;  // distance, in backward units, between units of one KV head that run on one XCD
   bool q_covered = false, kv_covered = false;  // every packed Q row / KV row belongs to some unit
   // device copies
   int device = -1;
