@@ -20,6 +20,8 @@ CA_ERR_INVALID_ARG, CA_ERR_UNSUPPORTED, CA_ERR_WORKSPACE, CA_ERR_HIP, CA_ERR_STA
 
 
 class CaError(RuntimeError):
+    """A negative ca_status from the library, with its code and the library's detail string."""
+
     def __init__(self, code: int, detail: str):
         super().__init__(f"ca_attention error {code}: {detail}")
         self.code = code
@@ -27,6 +29,8 @@ class CaError(RuntimeError):
 
 
 class BatchDesc(ctypes.Structure):
+    """ca_batch_desc of include/ca_attention.h."""
+
     _fields_ = [
         ("n_docs", ctypes.c_int32), ("n_tasks", ctypes.c_int32),
         ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
@@ -161,6 +165,7 @@ class Plan:
 
 
 def ca_plan_host(batch) -> Plan:
+    """Validate `batch` and build its launch schedule on the host only (no GPU needed)."""
     keep = []
     d = make_desc(batch, keep)
     h = ctypes.c_void_p()
@@ -169,6 +174,7 @@ def ca_plan_host(batch) -> Plan:
 
 
 def ca_plan(batch) -> Plan:
+    """ca_plan_host + upload of the schedule to the current device."""
     keep = []
     d = make_desc(batch, keep)
     h = ctypes.c_void_p()

@@ -80,6 +80,9 @@ def min_comm_head_tail(alpha: float, L_q: float, L_kv: float, L_doc: float, size
 # ------------------------------------------------------------------------------------------- scheduler
 @dataclass
 class Item:
+    """A whole document or a contiguous shard of one, resident on its home server; it maps one to one to a CA-task
+    (Section 4.2, "Item"): query rows q_pos .. q_pos + q_len - 1 of document `doc` with the prefix before them."""
+
     doc: int
     q_pos: int   # document position of the first query row
     q_len: int
@@ -87,20 +90,25 @@ class Item:
 
     @property
     def kv_len(self) -> int:
+        """Keys the Item's last row sees: its own rows plus the context before them."""
         return self.q_pos + self.q_len
 
     @property
     def pairs(self) -> int:
+        """Exact (query, key) pairs of the Item: its load, in units of one score."""
         return W.task_pairs(self.q_pos, self.q_len)
 
 
 @dataclass
 class Schedule:
+    """Result of `schedule`: which Items every attention server computes, and what moving them cost."""
+
     servers: list                      # per server: list of Items it computes
     moved_bytes: float = 0.0           # by the cost model (every move pays for its queries and its whole context)
     moves: list = field(default_factory=list)   # (source, destination, Item moved, bytes)
 
     def loads(self):
+        """Per-server load in (query, key) pairs."""
         return [sum(it.pairs for it in s) for s in self.servers]
 
     def imbalance(self) -> float:
