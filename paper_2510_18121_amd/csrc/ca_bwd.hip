@@ -13,6 +13,8 @@
 //            S = Q K^T, dP = dO V^T (K, V fragments of the wave's 32 keys stay in registers),
 //            dV^T += dO^T P, dK^T += Q^T dS   (Q^T, dO^T through transposing LDS reads)
 //          dK and dV are written once, already summed over the group's heads and all tasks of the document.
+//          Workgroups of one KV head that run on one XCD walk the same Q/dO tiles and pace each other through
+//          published step counts, so that the tiles are fetched into that XCD's L2 once ("convoy", see the kernel).
 // No atomics and no fp32 dQ buffer: the price is that S and dP are computed in both kernels (7 contractions
 // instead of the minimal 5).  Results are deterministic.
 #include <algorithm>
