@@ -241,3 +241,41 @@ def test_schedule_invariants_on_random_descriptors(seed):
         if rng.random() < 0.25:
             b.task_kv_len[t] = int(rng.integers(1, b.task_kv_len[t] + 1))
     check_schedule(b)
+
+
+def test_planning_from_several_threads_at_once():
+    """ca_plan_host keeps no global state (the scheduler plans the next batch on its own thread while the GPU runs
+    the current one, Section 4.1): four threads planning different batches concurrently get the plans a single thread
+    gets, and a failing call on one thread leaves the others' error strings alone."""
+    import threading
+    batches = [W.config(1), W.config(3, 16), W.config(5, 16), W.custom([5, 9, 700], [(0, 4, 1), (2, 300, 1)], 4, 4, 64)]
+    want = []
+    for b in batches:
+        p = B.ca_plan_host(b)
+        want.append((p.info(), p.rows()[0].copy(), p.fwd_units().copy(), p.bwd_units().copy()))
+    got, errs = [None] * len(batches), [None] * len(batches)
+
+    def work(i):
+        try:
+            for _ in range(5):
+                p = B.ca_plan_host(batches[i])
+                got[i] = (p.info(), p.rows()[0].copy(), p.fwd_units().copy(), p.bwd_units().copy())
+                if i == 0:  # interleave failing calls
+                    try:
+                        B.ca_plan_host(mutated(n_q_heads=7))
+                        raise AssertionError("a head ratio of 7/2 was accepted")
+                    except B.CaError as e:
+                        assert "multiple" in e.detail, e.detail
+        except BaseException as ex:  # noqa: BLE001 - reported by the main thread below
+            errs[i] = ex
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(len(batches))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert errs == [None] * len(batches), errs
+    for g, w in zip(got, want):
+        assert g[0] == w[0]
+        for a, b_ in zip(g[1:], w[1:]):
+            assert np.array_equal(a, b_)
