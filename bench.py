@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="after the timed steps, run one plain device copy of this many MiB (a kernel of known "
                          "traffic next to which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled)")
+    ap.add_argument("--no-sustained-probe", action="store_true",
+                    help="skip the MFMA-only launches that measure the matrix pipes' sustained rate on this device")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported "
@@ -112,6 +114,14 @@ def main():
             kern[kk].append(r[kk])
     kavg = {kk: sum(vv) / len(vv) for kk, vv in kern.items()}
     plan.profile_enable(False)
+    # what the matrix pipes sustain on this device, right after the timed work (chip warm): the library's MFMA-only
+    # kernel on N(0,1) bf16 operands, one wave per SIMD like the dK/dV kernel, three launches of about a quarter second
+    # each, the last one reported; then the same with an attention kernel's other per-MFMA work issued alongside
+    sustained = sustained_side = None
+    if not args.no_sustained_probe:
+        from paper_2510_18121_amd import mfma_rate
+        sustained = mfma_rate.sustained_tflops("normal", 0, 1, device=dev)[-1]
+        sustained_side = mfma_rate.sustained_tflops("normal", 1, 1, device=dev)[-1]
     if args.calibration_copy_mib > 0:
         src = torch.empty(args.calibration_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(3)
         dst = torch.empty_like(src)
@@ -146,6 +156,17 @@ def main():
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": bwd_main_tflops / PEAK_BF16_TFLOPS,
                      "traffic": DKV_TRAFFIC_BYTES_CFG3 if args.workload == 3 else None},
     }
+    # The metric credits 14*D flops per (pair, head); the kernels execute 18*D (the dK/dV and the dQ kernel both
+    # recompute S and dP).  Executed rate next to the rate of back-to-back MFMAs measured in this run:
+    executed = (fl["fwd"] + 1.4 * fl["bwd"]) / (ms_per_step * 1e-3) / 1e12
+    out["executed_tflops"] = executed
+    if sustained is not None:
+        out["roofline"]["sustained_mfma"] = {
+            "tflops": sustained, "frac": bwd_main_tflops / sustained,
+            "with_side_work_tflops": sustained_side, "frac_with_side_work": bwd_main_tflops / sustained_side,
+            "what": "ca_mfma_stream in this run after the timed steps: v_mfma_f32_32x32x16_bf16 back to back from "
+                    "registers, N(0,1) bf16 operands, one wave per SIMD on all CUs; with_side_work adds one 16-byte "
+                    "LDS read per lane and two multiply-adds per MFMA and one exponential per two MFMAs"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(out), flush=True)

@@ -155,6 +155,28 @@ int ca_sum_partial_dq(const int32_t *part_rows, int64_t n_rows, int32_t n_parts,
 int ca_profile_enable(ca_plan_t *plan, int on);
 int ca_profile_read(ca_plan_t *plan, float *out_ms);
 
+/*
+ * ca_mfma_stream: calibration aid for the matrix-pipe roofline, not a step of the method.  Launches n_workgroups
+ * workgroups of four waves; every wave issues n_mfma_per_wave v_mfma_f32_32x32x16_bf16 (the instruction the three
+ * attention kernels are built on) back to back from registers, with no memory access in the loop.  Timed by the
+ * caller over enough workgroups to fill the chip (HIP events on hip_stream around the call), it gives the rate the
+ * matrix pipes sustain on this device for this kind of operand data and this many waves per SIMD:
+ * n_workgroups * 4 * n_mfma_per_wave * 32768 flops per launch.
+ *   operands : device, bf16 [16][256][8] (64 KiB), read only: thread t of every workgroup takes fragment 2i as its
+ *              i-th A operand and fragment 2i+1 as its i-th B operand (i = 0..7), 8 values each; MFMA number
+ *              64 n + 8 r + j of a wave multiplies A[j] by B[(j + r) mod 8] into accumulation chain j mod 4.
+ *   n_mfma_per_wave : a non-negative multiple of 64.
+ *   side_work : 0 = MFMAs only.  1 or 2 = every MFMA is followed by the other work an attention kernel issues per
+ *              MFMA, results unused: one 16-byte LDS read per lane and 2 (4) fp32 multiply-adds, plus one
+ *              exponential per two MFMAs (per MFMA): about the dK/dV (forward) kernel's ratio.  Uses 16 KiB of LDS.
+ *   sums     : device, fp32 [n_workgroups][256], written: per thread the sum of its 64 accumulator values (with
+ *              all-ones operands exactly 256 * n_mfma_per_wave as long as that is below 2^24), so a caller can
+ *              check that the instructions ran.
+ * Asynchronous on hip_stream, allocates nothing.  CA_ERR_INVALID_ARG for a bad count or a null pointer.
+ */
+int ca_mfma_stream(const void *operands, int64_t n_mfma_per_wave, int32_t n_workgroups, int32_t side_work, float *sums,
+                   void *hip_stream);
+
 const char *ca_error_string(int code);
 const char *ca_last_error(void); /* thread-local detail of the last failing call on this thread */
 

@@ -72,6 +72,7 @@ def lib() -> ctypes.CDLL:
         i32, i64 = ctypes.c_int32, ctypes.c_int64
         L.ca_merge_partials.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, vp, vp, i32, i32, vp]
         L.ca_sum_partial_dq.argtypes = [vp, i64, i32, vp, i64, vp, i32, i32, vp]
+        L.ca_mfma_stream.argtypes = [vp, i64, i32, i32, vp, vp]
         _lib = L
     return _lib
 
@@ -265,3 +266,13 @@ def ca_sum_partial_dq(part_rows, dq_part, dq, stream=None):
     _expect(dq_part, (tq, hq, d), torch.bfloat16, "dq_part")
     _expect(dq, (n_rows, hq, d), torch.bfloat16, "dq")
     _check(lib().ca_sum_partial_dq(_p(part_rows), n_rows, n_parts, _p(dq_part), tq, _p(dq), hq, d, _stream_ptr(stream)))
+
+
+def ca_mfma_stream(operands, n_mfma_per_wave, sums, side_work=0, stream=None):
+    """Back-to-back bf16 MFMAs from registers in sums.shape[0] workgroups (a calibration aid; see the header)."""
+    import torch
+    _expect(operands, (16, 256, 8), torch.bfloat16, "operands")
+    n_wg = sums.shape[0]
+    _expect(sums, (n_wg, 256), torch.float32, "sums")
+    _check(lib().ca_mfma_stream(_p(operands), int(n_mfma_per_wave), n_wg, int(side_work), _p(sums),
+                                _stream_ptr(stream)))

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libca_attention.so")
-SOURCES = ["ca_plan.cpp", "ca_api.hip", "ca_fwd.hip", "ca_bwd.hip", "ca_merge.hip"]
+SOURCES = ["ca_plan.cpp", "ca_api.hip", "ca_fwd.hip", "ca_bwd.hip", "ca_merge.hip", "ca_calib.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed fp32 VALU forms are kept out of the generated code on purpose

@@ -20,7 +20,7 @@ def test_header_functions_are_exported():
     assert {"ca_plan", "ca_plan_host", "ca_plan_upload", "ca_forward", "ca_backward", "ca_plan_destroy",
             "ca_plan_workspace_bytes", "ca_error_string", "ca_last_error", "ca_profile_enable",
             "ca_profile_read", "ca_plan_info", "ca_plan_rows", "ca_plan_fwd_units", "ca_plan_bwd_units",
-            "ca_merge_partials", "ca_sum_partial_dq"} <= set(names)
+            "ca_merge_partials", "ca_sum_partial_dq", "ca_mfma_stream"} <= set(names)
     lib = ctypes.CDLL(B.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -57,3 +57,16 @@ def test_merge_entry_points_reject_bad_arguments_on_the_host():
     assert lib.ca_sum_partial_dq(None, 4, 2, None, 4, None, 2, 64, None) == B.CA_ERR_INVALID_ARG
     # nothing to do: no launch, no error
     assert lib.ca_merge_partials(None, 0, 1, None, None, 0, None, None, None, None, 2, 64, None) == B.CA_OK
+
+
+def test_mfma_stream_rejects_bad_arguments_on_the_host():
+    lib = B.lib()
+    assert lib.ca_mfma_stream(None, 65, 4, 0, None, None) == B.CA_ERR_INVALID_ARG
+    assert b"multiple of 64" in lib.ca_last_error()
+    assert lib.ca_mfma_stream(None, -64, 4, 0, None, None) == B.CA_ERR_INVALID_ARG
+    assert lib.ca_mfma_stream(None, 64, -1, 0, None, None) == B.CA_ERR_INVALID_ARG
+    assert lib.ca_mfma_stream(None, 64, 4, 3, None, None) == B.CA_ERR_INVALID_ARG
+    assert b"side_work" in lib.ca_last_error()
+    assert lib.ca_mfma_stream(None, 64, 4, 0, None, None) == B.CA_ERR_INVALID_ARG
+    assert b"null" in lib.ca_last_error()
+    assert lib.ca_mfma_stream(None, 64, 0, 0, None, None) == B.CA_OK
