@@ -25,6 +25,70 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 DKV_TRAFFIC_BYTES_CFG3 = int((27.3 + 0.56) * 2**30)
 
 
+class EngineClockSampler:
+    """Reads the engine clock (and the package power, where the driver exposes it) from sysfs every 20 ms on a host
+    thread while a section of the benchmark runs.  Read-only; every failure just leaves the figures at None."""
+
+    def __init__(self):
+        import glob
+        self.sclk = next(iter(sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))), None)
+        dev = os.path.dirname(self.sclk) if self.sclk else None
+        self.power = next(iter(sorted(glob.glob(dev + "/hwmon/hwmon*/power1_average") +
+                                      glob.glob(dev + "/hwmon/hwmon*/power1_input"))), None) if dev else None
+        cap = next(iter(sorted(glob.glob(dev + "/hwmon/hwmon*/power1_cap"))), None) if dev else None
+        self.power_cap_w = self._read_number(cap, 1e-6)
+        self.max_mhz = None
+        try:
+            self.max_mhz = max(float(l.split(":")[1].lower().replace("mhz", "").replace("*", "").strip())
+                               for l in open(self.sclk).read().splitlines() if ":" in l)
+        except Exception:
+            pass
+
+    @staticmethod
+    def _read_number(path, scale):
+        try:
+            return float(open(path).read().split()[0]) * scale
+        except Exception:
+            return None
+
+    def _current_mhz(self):
+        try:
+            for l in open(self.sclk).read().splitlines():
+                if "*" in l:
+                    return float(l.split(":")[1].lower().replace("mhz", "").replace("*", "").strip())
+        except Exception:
+            pass
+        return None
+
+    def __enter__(self):
+        import threading
+        self.mhz, self.watts, self._stop = [], [], threading.Event()
+
+        def run():
+            while not self._stop.is_set():
+                c, w = self._current_mhz(), self._read_number(self.power, 1e-6)
+                if c is not None:
+                    self.mhz.append(c)
+                if w is not None:
+                    self.watts.append(w)
+                self._stop.wait(0.02)
+        self._thread = threading.Thread(target=run, daemon=True)
+        if self.sclk:
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        if self.sclk:
+            self._thread.join()
+
+    def summary(self):
+        med = lambda x: sorted(x)[len(x) // 2] if x else None
+        return {"engine_clock_mhz_median": med(self.mhz), "engine_clock_mhz_min": min(self.mhz) if self.mhz else None,
+                "engine_clock_mhz_max": max(self.mhz) if self.mhz else None, "samples": len(self.mhz),
+                "power_w_median": med(self.watts), "power_cap_w": self.power_cap_w}
+
+
 def cpu_baseline(index: int):
     """The fp64 oracle, as it stands, timed on this host's cores on a bounded sample of the workload:
     the generator's token-count/8 twin (token-count/32 for the 512K workload) restricted to one KV head's
@@ -97,12 +161,14 @@ def main():
     torch.cuda.synchronize()
     plan.profile_enable(True)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    clocks = EngineClockSampler()
     wall0 = time.perf_counter()
-    e0.record()
-    for _ in range(args.steps):
-        step()
-    e1.record()
-    torch.cuda.synchronize()
+    with clocks:
+        e0.record()
+        for _ in range(args.steps):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
     wall = time.perf_counter() - wall0
     ms_per_step = e0.elapsed_time(e1) / args.steps
     # per-kernel durations: HIP events recorded by the library on the launch stream, one more pass
@@ -120,7 +186,9 @@ def main():
     sustained = sustained_side = None
     if not args.no_sustained_probe:
         from paper_2510_18121_amd import mfma_rate
-        sustained = mfma_rate.sustained_tflops("normal", 0, 1, device=dev)[-1]
+        probe_clocks = EngineClockSampler()
+        with probe_clocks:
+            sustained = mfma_rate.sustained_tflops("normal", 0, 1, device=dev)[-1]
         sustained_side = mfma_rate.sustained_tflops("normal", 1, 1, device=dev)[-1]
     if args.calibration_copy_mib > 0:
         src = torch.empty(args.calibration_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(3)
@@ -132,8 +200,9 @@ def main():
     tflops = fl["total"] / (ms_per_step * 1e-3) / 1e12
     bwd_ms = kavg["bwd_prep_ms"] + kavg["bwd_dkv_ms"] + kavg["bwd_dq_ms"]
     bwd_tflops = fl["bwd"] / (bwd_ms * 1e-3) / 1e12 if bwd_ms > 0 else 0.0
-    clock_mhz = getattr(props, "clock_rate", 0) / 1e3
-    # 4096 dense bf16 flops per clock per CU; None when the runtime does not report the engine clock
+    # the maximum engine clock: from the runtime's device properties, else the highest level the driver lists in sysfs
+    clock_mhz = getattr(props, "clock_rate", 0) / 1e3 or clocks.max_mhz or 0.0
+    # 4096 dense bf16 flops per clock per CU; None when neither source reports the engine clock
     peak_from_device = props.multi_processor_count * 4096 * clock_mhz * 1e6 / 1e12 if clock_mhz > 0 else None
     # the dK/dV kernel executes 4 of the backward's contractions (S, dP, dV, dK): 8*D*Hq*pairs flops
     dkv_flops = fl["bwd"] * 0.8
@@ -149,7 +218,7 @@ def main():
                    "flops_fwd_bwd": fl["total"]},
         "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
         "device": {"name": props.name, "cus": props.multi_processor_count, "clock_mhz": clock_mhz,
-                   "peak_bf16_tflops_from_device": peak_from_device},
+                   "peak_bf16_tflops_from_device": peak_from_device, "during_timed_steps": clocks.summary()},
         "kernels_ms": kavg, "fwd_only_tflops": fwd_tflops, "bwd_only_tflops": bwd_tflops, "plan_ms": plan_ms,
         "wall_s_timed": wall,
         "roofline": {"kernel": "ca_bwd_dkv_kernel", "bound": "mfma", "achieved": bwd_main_tflops,
@@ -163,7 +232,7 @@ def main():
     if sustained is not None:
         out["roofline"]["sustained_mfma"] = {
             "tflops": sustained, "frac": bwd_main_tflops / sustained,
-            "with_side_work_tflops": sustained_side, "frac_with_side_work": bwd_main_tflops / sustained_side,
+            "during_probe": probe_clocks.summary(), "with_side_work_tflops": sustained_side, "frac_with_side_work": bwd_main_tflops / sustained_side,
             "what": "ca_mfma_stream in this run after the timed steps: v_mfma_f32_32x32x16_bf16 back to back from "
                     "registers, N(0,1) bf16 operands, one wave per SIMD on all CUs; with_side_work adds one 16-byte "
                     "LDS read per lane and two multiply-adds per MFMA and one exponential per two MFMAs"}
