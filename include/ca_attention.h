@@ -83,10 +83,12 @@ typedef struct {
 int ca_plan_host(const ca_batch_desc *desc, ca_plan_t **out);
 
 /* ca_plan_upload: allocate the plan's small device arrays on the current device and copy the schedule
- * (asynchronously on `hip_stream`, a hipStream_t or NULL for the default stream). */
+ * (asynchronously on `hip_stream`, a hipStream_t or NULL for the default stream).  Launches that use the plan must
+ * be ordered after that copy: issue them on the same stream, or synchronise it first. */
 int ca_plan_upload(ca_plan_t *plan, void *hip_stream);
 
-/* ca_plan = ca_plan_host + ca_plan_upload on the default stream. */
+/* ca_plan = ca_plan_host + ca_plan_upload on the default stream + a wait for the copy: the plan it returns may be
+ * used on any stream. */
 int ca_plan(const ca_batch_desc *desc, ca_plan_t **out);
 
 /* Bytes of caller-provided device workspace ca_forward / ca_backward need (either pointer may be NULL). */

@@ -104,6 +104,10 @@ int ca_plan(const ca_batch_desc *desc, ca_plan_t **out) {
   int rc = ca_plan_host(desc, out);
   if (rc != CA_OK) return rc;
   rc = ca_plan_upload(*out, nullptr);
+  if (rc == CA_OK) {  // callers launch on streams of their own: the schedule must have landed before they do
+    const hipError_t e = hipStreamSynchronize(nullptr);
+    if (e != hipSuccess) rc = ca::hip_fail("plan upload", e);
+  }
   if (rc != CA_OK) {
     ca_plan_destroy(*out);
     *out = nullptr;
