@@ -11,8 +11,12 @@
  * recomputes P from it (Section 2.1: P is never materialised).
  *
  * All tensor pointers are DEVICE pointers owned by the caller; all descriptor arrays are HOST
- * pointers.  No entry point synchronises the device or throws; every one returns CA_OK (0) or a
- * negative ca_status, and ca_last_error() then holds a human-readable detail for the calling thread.
+ * pointers.  No entry point throws; every one returns CA_OK (0) or a negative ca_status, and ca_last_error()
+ * then holds a human-readable detail for the calling thread.  The launch calls (ca_forward, ca_backward,
+ * ca_merge_partials, ca_sum_partial_dq, ca_mfma_stream) never synchronise the device; ca_plan waits for its own
+ * upload and ca_profile_read for the events it reads.  A plan is read-only for the launch calls and may serve several
+ * host threads and streams at once, each launch with a workspace of its own (while profiling is enabled on it, one
+ * thread and one stream at a time: the timing events belong to the plan).
  *
  * Layouts (row-major, token-major, bf16 unless stated):
  *   Q, O, dO, dQ : [total_q ][n_q_heads ][head_dim]
@@ -111,7 +115,7 @@ int ca_forward(const ca_plan_t *plan, const void *q, const void *k, const void *
  * (bwd_bytes is about 2 * n_q_heads * padded_rows * (4 + 2 * head_dim) bytes: a little over the size of Q plus dO),
  * and one 4-byte progress counter per backward work unit, through which workgroups that read the same Q/dO tiles pace
  * each other (timing only).  No arithmetic uses atomics: results are bit-reproducible from run to run.  Allocates
- * nothing, never synchronises.
+ * nothing, never synchronises.  Two calls whose workspaces overlap must not overlap in time on the device.
  */
 int ca_backward(const ca_plan_t *plan, const void *q, const void *k, const void *v, const void *o,
                 const void *d_o, const float *lse, void *dq, void *dk, void *dv,
