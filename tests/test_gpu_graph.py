@@ -56,3 +56,41 @@ def test_forward_backward_and_merge_replay_from_a_graph():
     step()
     torch.cuda.synchronize()
     assert torch.equal(got, o)
+
+
+def test_one_plan_serves_two_streams_with_a_workspace_each():
+    """The launch calls only read the plan: two streams run forward and backward on it at the same time, each with
+    inputs, outputs and a workspace of its own, and get what each gets alone."""
+    b = W.one_kv_group(W.config(2, 4))
+    plan = B.ca_plan(b)
+    streams = [torch.cuda.Stream(device=DEV) for _ in range(2)]
+    sets = []
+    for i in range(2):
+        q, k, v, d_o = W.make_tensors(b, DEV)
+        if i:
+            q, k = (q * 0.5).contiguous(), (k * 1.5).contiguous()
+        ws = B.alloc_workspace(plan, DEV)
+        o, dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        lse = torch.empty((b.n_q_heads, b.total_q), dtype=torch.float32, device=DEV)
+        sets.append((q, k, v, d_o, o, lse, dq, dk, dv, ws))
+
+    def run(i, stream):
+        q, k, v, d_o, o, lse, dq, dk, dv, ws = sets[i]
+        B.ca_forward(plan, q, k, v, o, lse, ws, stream=stream)
+        B.ca_backward(plan, q, k, v, o, d_o, lse, dq, dk, dv, ws, stream=stream)
+
+    want = []
+    for i in range(2):  # alone, on the current stream
+        run(i, None)
+        torch.cuda.synchronize()
+        want.append([t.clone() for t in sets[i][4:9]])
+        for t in sets[i][4:9]:
+            t.fill_(float("nan"))
+    torch.cuda.synchronize()
+    for rep in range(3):  # together
+        for i in range(2):
+            run(i, streams[i])
+        torch.cuda.synchronize()
+        for i in range(2):
+            for t, w in zip(sets[i][4:9], want[i]):
+                assert torch.equal(t, w), f"stream {i}, repetition {rep}"
