@@ -35,6 +35,7 @@ class EngineClockSampler:
         dev = os.path.dirname(self.sclk) if self.sclk else None
         self.power = next(iter(sorted(glob.glob(dev + "/hwmon/hwmon*/power1_average") +
                                       glob.glob(dev + "/hwmon/hwmon*/power1_input"))), None) if dev else None
+        self.temps = sorted(glob.glob(dev + "/hwmon/hwmon*/temp*_input")) if dev else []
         cap = next(iter(sorted(glob.glob(dev + "/hwmon/hwmon*/power1_cap"))), None) if dev else None
         self.power_cap_w = self._read_number(cap, 1e-6)
         self.max_mhz = None
@@ -62,7 +63,7 @@ class EngineClockSampler:
 
     def __enter__(self):
         import threading
-        self.mhz, self.watts, self._stop = [], [], threading.Event()
+        self.mhz, self.watts, self.temp_c, self._stop = [], [], [], threading.Event()
 
         def run():
             while not self._stop.is_set():
@@ -71,6 +72,9 @@ class EngineClockSampler:
                     self.mhz.append(c)
                 if w is not None:
                     self.watts.append(w)
+                t = [x for x in (self._read_number(f, 1e-3) for f in self.temps) if x is not None]
+                if t:
+                    self.temp_c.append(max(t))  # the hottest of the sensors the driver lists
                 self._stop.wait(0.02)
         self._thread = threading.Thread(target=run, daemon=True)
         if self.sclk:
@@ -86,7 +90,8 @@ class EngineClockSampler:
         med = lambda x: sorted(x)[len(x) // 2] if x else None
         return {"engine_clock_mhz_median": med(self.mhz), "engine_clock_mhz_min": min(self.mhz) if self.mhz else None,
                 "engine_clock_mhz_max": max(self.mhz) if self.mhz else None, "samples": len(self.mhz),
-                "power_w_median": med(self.watts), "power_cap_w": self.power_cap_w}
+                "power_w_median": med(self.watts), "power_cap_w": self.power_cap_w,
+                "hottest_sensor_c_median": med(self.temp_c)}
 
 
 def cpu_baseline(index: int):
