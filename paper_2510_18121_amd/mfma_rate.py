@@ -6,6 +6,7 @@ on operands of a chosen kind and returns TFLOP/s: the rate the attention kernels
 with, next to the published peak their roofline fraction is quoted against.
 
     python -m paper_2510_18121_amd.mfma_rate          # a table over operand data, side work and waves per SIMD
+    python -m paper_2510_18121_amd.mfma_rate --kind normal --side-work 1 --launches 3     # one line of it
 """
 from __future__ import annotations
 
@@ -64,11 +65,20 @@ def sustained_tflops(kind: str = "normal", side_work: int = 0, workgroups_per_cu
 
 
 def main():
-    print("operands  side_work  workgroups/CU   TFLOP/s of five back-to-back launches of about 0.25 s")
-    for kind, side, wpc in (("normal", 0, 1), ("normal", 0, 2), ("normal", 0, 8), ("normal", 1, 1), ("normal", 1, 2),
-                            ("normal", 2, 1), ("normal", 2, 2), ("zeros", 0, 1), ("ones", 0, 1), ("softmax", 0, 1),
-                            ("normal", 0, 1)):
-        r = sustained_tflops(kind, side, wpc, launches=5)
+    import argparse
+    ap = argparse.ArgumentParser(description="sustained bf16 MFMA rate of the device (ca_mfma_stream)")
+    ap.add_argument("--kind", choices=KINDS, help="operand data; without it a table over kinds, side work and occupancy")
+    ap.add_argument("--side-work", type=int, default=0, choices=(0, 1, 2))
+    ap.add_argument("--workgroups-per-cu", type=int, default=1)
+    ap.add_argument("--launches", type=int, default=5)
+    args = ap.parse_args()
+    table = (("normal", 0, 1), ("normal", 0, 2), ("normal", 0, 8), ("normal", 1, 1), ("normal", 1, 2), ("normal", 2, 1),
+             ("normal", 2, 2), ("zeros", 0, 1), ("ones", 0, 1), ("softmax", 0, 1), ("normal", 0, 1))
+    if args.kind:
+        table = ((args.kind, args.side_work, args.workgroups_per_cu),)
+    print(f"operands  side_work  workgroups/CU   TFLOP/s of {args.launches} back-to-back launches of about 0.25 s")
+    for kind, side, wpc in table:
+        r = sustained_tflops(kind, side, wpc, launches=args.launches)
         print(f"{kind:8s}  {side:9d}  {wpc:13d}   " + "  ".join(f"{x:7.1f}" for x in r), flush=True)
 
 
