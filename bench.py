@@ -29,9 +29,9 @@ class EngineClockSampler:
     """Reads the engine clock (and the package power, where the driver exposes it) from sysfs every 20 ms on a host
     thread while a section of the benchmark runs.  Read-only; every failure just leaves the figures at None."""
 
-    def __init__(self):
+    def __init__(self, drm_root="/sys/class/drm"):
         import glob
-        self.sclk = next(iter(sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))), None)
+        self.sclk = next(iter(sorted(glob.glob(drm_root + "/card*/device/pp_dpm_sclk"))), None)
         dev = os.path.dirname(self.sclk) if self.sclk else None
         self.power = next(iter(sorted(glob.glob(dev + "/hwmon/hwmon*/power1_average") +
                                       glob.glob(dev + "/hwmon/hwmon*/power1_input"))), None) if dev else None
