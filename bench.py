@@ -195,6 +195,9 @@ def main():
         with probe_clocks:
             sustained = mfma_rate.sustained_tflops("normal", 0, 1, device=dev)[-1]
         sustained_side = mfma_rate.sustained_tflops("normal", 1, 1, device=dev)[-1]
+        # the other two kernels run two waves per SIMD: the dQ kernel's side work is about level 1, the forward's level 2
+        sustained_dq = mfma_rate.sustained_tflops("normal", 1, 2, device=dev)[-1]
+        sustained_fwd = mfma_rate.sustained_tflops("normal", 2, 2, device=dev)[-1]
     if args.calibration_copy_mib > 0:
         src = torch.empty(args.calibration_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(3)
         dst = torch.empty_like(src)
@@ -213,6 +216,8 @@ def main():
     dkv_flops = fl["bwd"] * 0.8
     bwd_main_tflops = dkv_flops / (kavg["bwd_dkv_ms"] * 1e-3) / 1e12 if kavg["bwd_dkv_ms"] > 0 else 0.0
     fwd_tflops = fl["fwd"] / (kavg["fwd_kernel_ms"] * 1e-3) / 1e12 if kavg["fwd_kernel_ms"] > 0 else 0.0
+    # the dQ kernel executes 3 contractions (S, dP, dQ): 6*D*Hq*pairs flops
+    dq_tflops = fl["bwd"] * 0.6 / (kavg["bwd_dq_ms"] * 1e-3) / 1e12 if kavg["bwd_dq_ms"] > 0 else 0.0
     out = {
         "metric": "core-attention fwd+bwd TFLOP/s (causal FLOPs), 1 GPU",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -237,7 +242,13 @@ def main():
     if sustained is not None:
         out["roofline"]["sustained_mfma"] = {
             "tflops": sustained, "frac": bwd_main_tflops / sustained,
-            "during_probe": probe_clocks.summary(), "with_side_work_tflops": sustained_side, "frac_with_side_work": bwd_main_tflops / sustained_side,
+            "during_probe": probe_clocks.summary(), "with_side_work_tflops": sustained_side,
+            "frac_with_side_work": bwd_main_tflops / sustained_side,
+            "other_kernels": {
+                "ca_fwd_kernel": {"executed_tflops": fwd_tflops, "stream_two_waves_side_work_2_tflops": sustained_fwd,
+                                  "frac": fwd_tflops / sustained_fwd},
+                "ca_bwd_dq_kernel": {"executed_tflops": dq_tflops, "stream_two_waves_side_work_1_tflops": sustained_dq,
+                                     "frac": dq_tflops / sustained_dq}},
             "what": "ca_mfma_stream in this run after the timed steps: v_mfma_f32_32x32x16_bf16 back to back from "
                     "registers, N(0,1) bf16 operands, one wave per SIMD on all CUs; with_side_work adds one 16-byte "
                     "LDS read per lane and two multiply-adds per MFMA and one exponential per two MFMAs"}
