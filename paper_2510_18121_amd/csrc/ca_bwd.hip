@@ -571,7 +571,10 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
         }
         __builtin_amdgcn_sched_barrier(0);
       }
-      mfma_settle(sw, dpw, ndt);
+      // In the loop the tuples written here are next read by the vector ALU a whole phase B (16 MFMAs) later, and the
+      // tuples the following chain overwrites were last read in that phase B: only the first call needs wait states.
+      if (vec) mfma_chain_end(sw, dpw, ndt);
+      else mfma_settle(sw, dpw, ndt);
     };
 
     // blocks 0 and 1 have landed (this wave's part); block 2 and the issued part of block 3 may be in flight

@@ -213,6 +213,12 @@ __device__ __forceinline__ void mfma_settle(f32x16 &x, f32x16 &y) { asm volatile
 __device__ __forceinline__ void mfma_settle(f32x16 &x, f32x16 &y, const f32x16 &c) {
   asm volatile("s_nop 11" : "+v"(x), "+v"(y) : "v"(c));
 }
+// End of a chain whose first non-MFMA reader is known to be at least a whole phase of MFMAs away (the pipelined loop of
+// the dK/dV kernel): no wait states are needed, only the ordering of mfma_settle().  The comment is what the build's
+// static check of the instruction stream looks for.
+__device__ __forceinline__ void mfma_chain_end(f32x16 &x, f32x16 &y, const f32x16 &c) {
+  asm volatile("; chain end" : "+v"(x), "+v"(y) : "v"(c));
+}
 __device__ __forceinline__ void pin(float &v) { asm volatile("" : "+v"(v)); }
 // exp2(x * c - g) as one volatile asm statement: like pin() it stays where it is written in the instruction stream
 // (between the MFMAs of its slot), but without the wait state the compiler puts between an empty asm that "defines"
