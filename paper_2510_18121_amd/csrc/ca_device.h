@@ -214,8 +214,9 @@ __device__ __forceinline__ void mfma_settle(f32x16 &x, f32x16 &y, const f32x16 &
   asm volatile("s_nop 11" : "+v"(x), "+v"(y) : "v"(c));
 }
 // End of a chain whose first non-MFMA reader is known to be at least a whole phase of MFMAs away (the pipelined loop of
-// the dK/dV kernel): no wait states are needed, only the ordering of mfma_settle().  The comment is what the build's
-// static check of the instruction stream looks for.
+// the dK/dV kernel): no wait states are needed, only the ordering of mfma_settle().  The assembly comment is what
+// the static check of the generated instruction stream (isa_check.py, run by the CPU tests) looks for: it verifies that
+// nothing but MFMAs touches the tuples for the next 16 issue cycles.
 __device__ __forceinline__ void mfma_chain_end(f32x16 &x, f32x16 &y, const f32x16 &c) {
   asm volatile("; chain end" : "+v"(x), "+v"(y) : "v"(c));
 }
