@@ -337,8 +337,8 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   const int64_t block_stride = int64_t(Hq) * head_stride;  // ... of consecutive blocks, same head
   const int64_t tile0 = (int64_t(u.slot_begin / BWD_BQ + pblk) * Hq + hk * G) * head_stride;
   const char *q_tile = reinterpret_cast<const char *>(Qs) + tile0, *do_tile = reinterpret_cast<const char *>(dOs) + tile0;
-  // the wave's auxiliary array: log2e*LSE (wave 0), -Delta (wave 1), slot positions (wave 2; wave 3 repeats them
-  // into a spare area so that every wave issues the same number of loads)
+  // the wave's auxiliary array: log2e*LSE (wave 0), -Delta (wave 1), slot positions (wave 2); wave 3's load goes to
+  // a spare area, so that every wave issues the same number of loads, and brings the peers' progress counters (below)
   const int64_t aux_hstride = wave < 2 ? padded : 0;
   const int aux_bstep = wave == 3 ? 0 : BWD_BQ;
   const float *aux_ptr = (wave == 0 ? l2_slot + int64_t(hk) * G * padded
