@@ -22,7 +22,7 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 
 # HBM bytes per launch of the dK/dV kernel on workload 3, from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes whose
 # summary is profiles/hot_path_cfg3_hbm_traffic.md (counters scaled by the plain-copy calibration stated there)
-DKV_TRAFFIC_BYTES_CFG3 = int((27.3 + 0.56) * 2**30)
+DKV_TRAFFIC_BYTES_CFG3 = int((47.3 + 0.56) * 2**30)
 
 
 class EngineClockSampler:
