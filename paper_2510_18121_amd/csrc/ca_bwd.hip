@@ -18,6 +18,7 @@
 // No atomics and no fp32 dQ buffer: the price is that S and dP are computed in both kernels (7 contractions
 // instead of the minimal 5).  Results are deterministic.
 #include <algorithm>
+#include <atomic>
 
 #include "ca_device.h"
 #include "ca_internal.h"
@@ -783,12 +784,13 @@ static void launch_fill(void *p, size_t bytes, hipStream_t st) {
 }
 
 template <class F>
-static hipError_t set_smem(F kern, int bytes, int device, bool *done) {
-  if (!done[device & 15]) {
+static hipError_t set_smem(F kern, int bytes, int device, std::atomic<bool> *done) {
+  // once per device; two threads that meet here both set the same value, which is harmless
+  if (!done[device & 15].load(std::memory_order_acquire)) {
     hipError_t e =
         hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e != hipSuccess) return e;
-    done[device & 15] = true;
+    done[device & 15].store(true, std::memory_order_release);
   }
   return hipSuccess;
 }
@@ -821,7 +823,7 @@ static hipError_t launch_bwd_t(const ca_plan_t *p, const void *q, const void *k,
   if (ev) (void)hipEventRecord(ev[1], st);
   if (!p->bwd_units.empty()) {
     auto kern = ca_bwd_dkv_kernel<D>;
-    static bool done[16] = {};
+    static std::atomic<bool> done[16];
     hipError_t e = set_smem(kern, DkvSmem<D>::TOTAL, p->device, done);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(unsigned(p->bwd_units.size())), dim3(256), DkvSmem<D>::TOTAL, st, p->d_bwd_units,
@@ -833,7 +835,7 @@ static hipError_t launch_bwd_t(const ca_plan_t *p, const void *q, const void *k,
   if (ev) (void)hipEventRecord(ev[2], st);
   if (!p->fwd_units.empty()) {
     auto kern = ca_bwd_dq_kernel<D>;
-    static bool done[16] = {};
+    static std::atomic<bool> done[16];
     hipError_t e = set_smem(kern, DqSmem<D>::TOTAL, p->device, done);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(unsigned(p->fwd_units.size())), dim3(512), DqSmem<D>::TOTAL, st, p->d_fwd_units,

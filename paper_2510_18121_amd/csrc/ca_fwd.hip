@@ -19,6 +19,7 @@
 // independent matrix instructions.  That straight-line form is used for tiles entirely below the diagonal of
 // the wave's rows; diagonal tiles take a general path with masking.  The softmax runs in base 2 with
 // scale*log2(e) folded into one FMA and rescales the accumulators lazily.
+#include <atomic>
 #include <type_traits>
 
 #include "ca_device.h"
@@ -328,12 +329,12 @@ static hipError_t launch_fwd_t(const ca_plan_t *p, const void *q, const void *k,
                                hipStream_t st) {
   if (p->fwd_units.empty()) return hipSuccess;
   auto kern = ca_fwd_kernel<D>;
-  static bool attr_done[16] = {};
-  if (!attr_done[p->device & 15]) {
+  static std::atomic<bool> attr_done[16];  // once per device; a second thread repeating the call is harmless
+  if (!attr_done[p->device & 15].load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        FwdSmem<D>::TOTAL);
     if (e != hipSuccess) return e;
-    attr_done[p->device & 15] = true;
+    attr_done[p->device & 15].store(true, std::memory_order_release);
   }
   const float c = p->scale * 1.4426950408889634f;
   hipLaunchKernelGGL(kern, dim3(unsigned(p->fwd_units.size())), dim3(512), FwdSmem<D>::TOTAL, st, p->d_fwd_units,

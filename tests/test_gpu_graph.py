@@ -94,3 +94,46 @@ def test_one_plan_serves_two_streams_with_a_workspace_each():
         for i in range(2):
             for t, w in zip(sets[i][4:9], want[i]):
                 assert torch.equal(t, w), f"stream {i}, repetition {rep}"
+
+
+def test_one_plan_serves_four_host_threads():
+    """Four host threads launch forward and backward on one plan at the same time, each on a stream and with buffers of
+    its own (created beforehand); every thread gets the result of a lone call, bit for bit."""
+    import threading
+
+    b = W.one_kv_group(W.config(2, 8))
+    plan = B.ca_plan(b)
+    q, k, v, d_o = W.make_tensors(b, DEV)
+    ws = B.alloc_workspace(plan, DEV)
+    o, dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    lse = torch.empty((b.n_q_heads, b.total_q), dtype=torch.float32, device=DEV)
+    B.ca_forward(plan, q, k, v, o, lse, ws)
+    B.ca_backward(plan, q, k, v, o, d_o, lse, dq, dk, dv, ws)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (o, lse, dq, dk, dv)]
+    n = 4
+    streams = [torch.cuda.Stream(device=DEV) for _ in range(n)]
+    bufs = [[torch.full_like(t, float("nan")) for t in want] + [B.alloc_workspace(plan, DEV)] for _ in range(n)]
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(i):
+        try:
+            o_i, lse_i, dq_i, dk_i, dv_i, ws_i = bufs[i]
+            for _ in range(3):
+                B.ca_forward(plan, q, k, v, o_i, lse_i, ws_i, stream=streams[i])
+                B.ca_backward(plan, q, k, v, o_i, d_o, lse_i, dq_i, dk_i, dv_i, ws_i, stream=streams[i])
+            streams[i].synchronize()
+        except BaseException as e:  # noqa: BLE001 - reported by the main thread
+            errors.append((i, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(n)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not errors, errors
+    torch.cuda.synchronize()
+    for i in range(n):
+        for got, w in zip(bufs[i][:5], want):
+            assert torch.equal(got, w), f"thread {i}"
