@@ -124,7 +124,11 @@ int ca_profile_enable(ca_plan_t *p, int on) {
   if (on && !p->profile) {
     for (int i = 0; i < 6; ++i) {
       hipEvent_t e;
-      CA_HIP(hipEventCreate(&e));
+      const hipError_t rc = hipEventCreate(&e);
+      if (rc != hipSuccess) {  // leave nothing half-made behind
+        for (int j = 0; j < i; ++j) (void)hipEventDestroy(static_cast<hipEvent_t>(p->ev[j])), p->ev[j] = nullptr;
+        return hip_fail("hipEventCreate", rc);
+      }
       p->ev[i] = e;
     }
     p->profile = true;
