@@ -223,8 +223,9 @@ void schedule(ca_plan_t *p) {
   p->ws_off_qs = 2 * per;
   p->ws_off_dos = 2 * per + copy;
   // ... and one progress counter per backward unit (plus a block of zeros), by which the dK/dV workgroups that walk
-  // the same Q/dO tiles keep within an L2 window of each other.  Workgroup i runs on XCD i mod 8 and unit i has KV
-  // head i mod n_kv_heads, so units lcm(8, n_kv_heads) apart share both.
+  // the same Q/dO tiles keep within an L2 window of each other.  Workgroups go to the 8 XCDs round robin in index
+  // order (workgroup i to XCD (i + c) mod 8) and unit i has KV head i mod n_kv_heads, so units lcm(8, n_kv_heads)
+  // apart share both.
   p->ws_off_prog = 2 * per + 2 * copy;
   p->peer_stride = int(std::lcm<int64_t>(8, hkv));
   p->ws_bwd = p->ws_off_prog + (p->bwd_units.size() + 64) * sizeof(int32_t);

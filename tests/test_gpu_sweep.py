@@ -25,8 +25,8 @@ def test_shard_chunks_match_the_oracle(mode, n, ctx):
 
 def test_latency_grid_predicts_unmeasured_tasks():
     """A coarse grid measured on this GPU; tasks between grid points are then timed and compared with the model's
-    prediction.  The bound is loose on purpose (timing noise on a shared box); the model's arithmetic is pinned
-    by the CPU tests."""
+    prediction (bilinear in latency between grid points a factor of four apart: within 15 %; the model's arithmetic is
+    pinned by the CPU tests)."""
     from paper_2510_18121_amd.profiler import measure_grid, time_batch
 
     g = measure_grid([256, 1024, 4096], [1024, 4096, 16384], hq=8, hkv=2, d=128, steps=3, warmup=1)
@@ -36,7 +36,7 @@ def test_latency_grid_predicts_unmeasured_tasks():
         t = time_batch(b, steps=3, warmup=1) * 1e-3
         pred = g.predict(ql, kl)
         print(f"task q={ql} kv={kl}: measured {t * 1e6:.0f} us, predicted {pred * 1e6:.0f} us", flush=True)
-        assert 0.4 * t <= pred <= 2.5 * t
+        assert 0.85 * t <= pred <= 1.15 * t, (ql, kl, t, pred)
 
 
 def test_scheduled_servers_together_equal_the_single_call():
