@@ -183,6 +183,31 @@ int ca_profile_read(ca_plan_t *plan, float *out_ms);
 int ca_mfma_stream(const void *operands, int64_t n_mfma_per_wave, int32_t n_workgroups, int32_t side_work, float *sums,
                    void *hip_stream);
 
+/*
+ * ca_xcd_map: which XCD (each of the 8 has an L2 of its own) every workgroup of a launch of n_workgroups workgroups of
+ * threads_per_workgroup threads runs on: out[i] = hardware XCC id of workgroup i (device int32 [n_workgroups]).
+ * The work order of ca_plan (Section 3.2: throughput should depend on the aggregate tokens of a fused call) puts the
+ * units of one KV head on one XCD by assuming that workgroups are dealt to the XCDs round robin in index order
+ * (workgroup i to XCD (i + c) mod 8, c depending on where the previous launch stopped); tests read the mapping through this
+ * call.  Asynchronous on hip_stream, allocates nothing.
+ */
+int ca_xcd_map(int32_t n_workgroups, int32_t threads_per_workgroup, int32_t *out, void *hip_stream);
+
+/*
+ * ca_atomic_stream: calibration aid, not a step of the method: the cost of summing partial dQ tiles with fp32 atomic
+ * adds, which a backward kernel that owns KV tiles and computes S and dP only once (Section 2.1: P is recomputed in
+ * backward, once) would have to do.  n_workgroups workgroups of four waves run `steps` steps; per step every wave
+ * issues mfma_per_step v_mfma_f32_32x32x16_bf16 (a multiple of 4; fragments 0 and 1 of `operands`, laid out as for
+ * ca_mfma_stream) and atomics_per_step (0 .. 32) global_atomic_add_f32 of +1.0 per lane, 256 contiguous bytes per
+ * instruction, into its quarter of a 32 KiB tile; workgroup i uses region i mod 8 and tile (step + (i / 8) mod 8) mod
+ * n_tiles of it.
+ *   tiles : device fp32 [8][n_tiles][8192], read and written (after the launch its sum has grown by
+ *           n_workgroups * steps * atomics_per_step * 256);   sums : device fp32 [n_workgroups][256], written.
+ * Asynchronous on hip_stream, allocates nothing.  CA_ERR_INVALID_ARG for counts out of range or null pointers.
+ */
+int ca_atomic_stream(const void *operands, float *tiles, int32_t n_tiles, int32_t n_workgroups, int32_t steps,
+                     int32_t mfma_per_step, int32_t atomics_per_step, float *sums, void *hip_stream);
+
 const char *ca_error_string(int code);
 const char *ca_last_error(void); /* thread-local detail of the last failing call on this thread */
 

@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.ca_merge_partials.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, vp, vp, i32, i32, vp]
         L.ca_sum_partial_dq.argtypes = [vp, i64, i32, vp, i64, vp, i32, i32, vp]
         L.ca_mfma_stream.argtypes = [vp, i64, i32, i32, vp, vp]
+        L.ca_xcd_map.argtypes = [i32, i32, vp, vp]
+        L.ca_atomic_stream.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp]
         _lib = L
     return _lib
 
@@ -276,3 +278,22 @@ def ca_mfma_stream(operands, n_mfma_per_wave, sums, side_work=0, stream=None):
     _expect(sums, (n_wg, 256), torch.float32, "sums")
     _check(lib().ca_mfma_stream(_p(operands), int(n_mfma_per_wave), n_wg, int(side_work), _p(sums),
                                 _stream_ptr(stream)))
+
+
+def ca_xcd_map(n_workgroups, threads_per_workgroup=256, device="cuda", stream=None):
+    """XCD id of every workgroup of a launch of that shape (int32 tensor on the device)."""
+    import torch
+    out = torch.full((n_workgroups,), -1, dtype=torch.int32, device=device)
+    _check(lib().ca_xcd_map(int(n_workgroups), int(threads_per_workgroup), _p(out), _stream_ptr(stream)))
+    return out
+
+
+def ca_atomic_stream(operands, tiles, n_workgroups, steps, mfma_per_step, atomics_per_step, sums, stream=None):
+    """fp32 atomic adds into 32 KiB tiles next to an MFMA stream (a calibration aid; see the header)."""
+    import torch
+    _expect(operands, (16, 256, 8), torch.bfloat16, "operands")
+    n_tiles = tiles.shape[1]
+    _expect(tiles, (8, n_tiles, 8192), torch.float32, "tiles")
+    _expect(sums, (n_workgroups, 256), torch.float32, "sums")
+    _check(lib().ca_atomic_stream(_p(operands), _p(tiles), int(n_tiles), int(n_workgroups), int(steps),
+                                  int(mfma_per_step), int(atomics_per_step), _p(sums), _stream_ptr(stream)))
