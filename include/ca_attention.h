@@ -121,6 +121,23 @@ int ca_backward(const ca_plan_t *plan, const void *q, const void *k, const void 
                 const void *d_o, const float *lse, void *dq, void *dk, void *dv,
                 void *ws, size_t ws_bytes, void *hip_stream);
 
+/*
+ * ca_backward_static_ws: ca_backward for callers that can neither allocate device memory nor hold a workspace of
+ * their own: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and kernels as ca_backward, minus `ws`: the workspace is a device-resident array of
+ * CA_STATIC_WS_BYTES inside the library (every GPU the library runs on holds its own copy until the process
+ * ends; its address on the current device is looked up on the first call there, with no allocation).
+ * A batch whose ca_plan_workspace_bytes() backward figure exceeds CA_STATIC_WS_BYTES is refused with
+ * CA_ERR_WORKSPACE before anything is launched (with 32 query heads of 128 that is about 4000 padded query rows).
+ * All calls on one GPU share the one array, which keeps the previous call's contents (every launch rewrites
+ * what it reads): calls that overlap in time on one GPU - different streams, or threads - race, so issue them on one
+ * stream.  Calls no hipMalloc / hipFree, never synchronises.
+ */
+#define CA_STATIC_WS_BYTES (64u << 20)
+int ca_backward_static_ws(const ca_plan_t *plan, const void *q, const void *k, const void *v, const void *o,
+                          const void *d_o, const float *lse, void *dq, void *dk, void *dv, void *hip_stream);
+size_t ca_static_workspace_bytes(void); /* CA_STATIC_WS_BYTES as the loaded library was built */
+
 void ca_plan_destroy(ca_plan_t *plan);
 
 /*

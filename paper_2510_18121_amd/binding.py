@@ -56,6 +56,8 @@ def lib() -> ctypes.CDLL:
         L.ca_plan_workspace_bytes.argtypes = [vp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.ca_forward.argtypes = [vp] * 6 + [vp, sz, vp]
         L.ca_backward.argtypes = [vp] * 10 + [vp, sz, vp]
+        L.ca_backward_static_ws.argtypes = [vp] * 10 + [vp]
+        L.ca_static_workspace_bytes.restype = sz
         L.ca_plan_destroy.argtypes = [vp]
         L.ca_plan_destroy.restype = None
         L.ca_error_string.argtypes = [ctypes.c_int]
@@ -230,6 +232,19 @@ def ca_backward(plan: Plan, q, k, v, o, d_o, lse, dq, dk, dv, ws, stream=None):
     wsb = ws.numel() * ws.element_size() if ws is not None else 0
     _check(lib().ca_backward(plan.handle, _p(q), _p(k), _p(v), _p(o), _p(d_o), _p(lse), _p(dq), _p(dk), _p(dv),
                              _p(ws), wsb, _stream_ptr(stream)))
+
+
+def ca_backward_static_ws(plan: Plan, q, k, v, o, d_o, lse, dq, dk, dv, stream=None):
+    """ca_backward on the library's own device-resident workspace (for callers that may not allocate)."""
+    import torch
+    b = plan.batch
+    qs, ks = (b.total_q, b.n_q_heads, b.head_dim), (b.total_kv, b.n_kv_heads, b.head_dim)
+    for t, s, n in ((q, qs, "q"), (o, qs, "o"), (d_o, qs, "d_o"), (dq, qs, "dq"), (k, ks, "k"), (v, ks, "v"),
+                    (dk, ks, "dk"), (dv, ks, "dv")):
+        _expect(t, s, torch.bfloat16, n)
+    _expect(lse, (b.n_q_heads, b.total_q), torch.float32, "lse")
+    _check(lib().ca_backward_static_ws(plan.handle, _p(q), _p(k), _p(v), _p(o), _p(d_o), _p(lse), _p(dq), _p(dk),
+                                       _p(dv), _stream_ptr(stream)))
 
 
 def alloc_workspace(plan: Plan, device="cuda"):

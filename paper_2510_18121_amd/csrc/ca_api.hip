@@ -1,6 +1,7 @@
 // C-ABI entry points that touch the device: plan upload, forward and backward launches.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <sstream>
 
 #include "ca_internal.h"
@@ -22,6 +23,33 @@ static int hip_fail(const char *what, hipError_t e) {
     hipError_t e_ = (call);                           \
     if (e_ != hipSuccess) return hip_fail(#call, e_); \
   } while (0)
+
+// Device-resident backward workspace for callers that cannot allocate (ca_backward_static_ws).  In host code the
+// array's name is only a handle for hipGetSymbolAddress: the address each device holds its copy at is looked up once
+// per device and kept in static_ws_ptr; only that pointer is ever handed to kernels.
+static __device__ __align__(256) __attribute__((used)) unsigned char static_ws[CA_STATIC_WS_BYTES];
+static void *static_ws_ptr[16];
+static std::mutex static_ws_mutex;
+
+static int static_ws_on_device(int device, void **out) {
+  if (device < 0 || device >= 16) {
+    set_error("ca_backward_static_ws supports device ordinals 0..15");
+    return CA_ERR_UNSUPPORTED;
+  }
+  std::lock_guard<std::mutex> lock(static_ws_mutex);
+  if (!static_ws_ptr[device]) {  // the calling thread's current device is `device` (checked by the caller)
+    void *ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(static_ws));
+    if (e != hipSuccess) return hip_fail("hipGetSymbolAddress(static workspace)", e);
+    if (!ptr || reinterpret_cast<uintptr_t>(ptr) % 256 != 0) {
+      set_error("static workspace has no usable device address");
+      return CA_ERR_HIP;
+    }
+    static_ws_ptr[device] = ptr;
+  }
+  *out = static_ws_ptr[device];
+  return CA_OK;
+}
 
 static void free_device(ca_plan_t *p) {
   if (p->device < 0) return;
@@ -218,5 +246,25 @@ int ca_backward(const ca_plan_t *p, const void *q, const void *k, const void *v,
   if (p->profile) mp->ev_bwd = true;
   return CA_OK;
 }
+
+int ca_backward_static_ws(const ca_plan_t *p, const void *q, const void *k, const void *v, const void *o,
+                          const void *d_o, const float *lse, void *dq, void *dk, void *dv, void *hip_stream) {
+  using namespace ca;
+  int rc = check_call(p, nullptr, 0, 0);  // plan present, uploaded, and on the current device
+  if (rc != CA_OK) return rc;
+  if (p->ws_bwd > size_t(CA_STATIC_WS_BYTES)) {
+    std::ostringstream os;
+    os << "this batch needs a backward workspace of " << p->ws_bwd << " bytes; the static workspace holds "
+       << size_t(CA_STATIC_WS_BYTES) << " (use ca_backward with a caller-provided workspace)";
+    set_error(os.str());
+    return CA_ERR_WORKSPACE;
+  }
+  void *ws = nullptr;
+  rc = static_ws_on_device(p->device, &ws);
+  if (rc != CA_OK) return rc;
+  return ca_backward(p, q, k, v, o, d_o, lse, dq, dk, dv, ws, size_t(CA_STATIC_WS_BYTES), hip_stream);
+}
+
+size_t ca_static_workspace_bytes(void) { return size_t(CA_STATIC_WS_BYTES); }
 
 }  // extern "C"
