@@ -20,9 +20,11 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 
-# HBM bytes per launch of the dK/dV kernel on workload 3, from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes whose
-# summary is profiles/hot_path_cfg3_hbm_traffic.md (counters scaled by the plain-copy calibration stated there)
-DKV_TRAFFIC_BYTES_CFG3 = int((47.3 + 0.56) * 2**30)
+# HBM bytes per launch of the dK/dV kernel on workload 3 as counted by rocprofv3 (FETCH_SIZE / WRITE_SIZE passes,
+# scaled by the plain-copy calibration): NOT measured in a plain run of this script.  The figure of the last counter
+# passes is quoted under roofline.traffic_profiled with the file it comes from; roofline.traffic itself is null.
+DKV_TRAFFIC_PROFILED = {"bytes": int((47.3 + 0.56) * 2**30), "workload": 3,
+                        "source": "profiles/hot_path_cfg3_hbm_traffic.md"}
 
 
 class EngineClockSampler:
@@ -233,14 +235,18 @@ def main():
         "config": {"workload": b.name, "tokens": b.total_q, "n_q_heads": b.n_q_heads, "n_kv_heads": b.n_kv_heads,
                    "head_dim": b.head_dim, "docs": b.n_docs, "ca_tasks": b.n_tasks, "pairs": fl["pairs"],
                    "flops_fwd_bwd": fl["total"]},
-        "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
+        # against the peak read from the device (CUs x 4096 flop/clk x maximum engine clock); the published 2500 when
+        # the device reports no clock
+        "pct_of_bf16_mfma_peak": 100.0 * tflops / (peak_from_device or PEAK_BF16_TFLOPS),
+        "pct_peak_denominator_tflops": peak_from_device or PEAK_BF16_TFLOPS,
         "device": {"name": props.name, "cus": props.multi_processor_count, "clock_mhz": clock_mhz,
                    "peak_bf16_tflops_from_device": peak_from_device, "during_timed_steps": clocks.summary()},
         "kernels_ms": kavg, "fwd_only_tflops": fwd_tflops, "bwd_only_tflops": bwd_tflops, "plan_ms": plan_ms, "plan_first_call_ms": plan_first_ms,
         "wall_s_timed": wall,
         "roofline": {"kernel": "ca_bwd_dkv_kernel", "bound": "mfma", "achieved": bwd_main_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": bwd_main_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": DKV_TRAFFIC_BYTES_CFG3 if args.workload == 3 else None},
+                     "traffic": None,
+                     "traffic_profiled": DKV_TRAFFIC_PROFILED if args.workload == DKV_TRAFFIC_PROFILED["workload"] else None},
     }
     # The metric credits 14*D flops per (pair, head); the kernels execute 18*D (the dK/dV and the dQ kernel both
     # recompute S and dP).  Executed rate next to the rate of back-to-back MFMAs measured in this run:

@@ -77,11 +77,23 @@ class LatencyGrid:
         if all(np.isfinite(self.seconds[i, j]) and sat[i, j] for i, j, _ in corners):
             # saturation region: the kernel runs at its best measured rate
             return task_flops(q_len, kv_len, self.n_q_heads, self.head_dim, self.backward) / self.max_throughput()
-        # corners below the diagonal kv_len = q_len are unmeasured: their weight goes to the measured ones
-        tot = sum(w for i, j, w in corners if np.isfinite(self.seconds[i, j]))
-        if tot <= 0:
+        have = [(i, j, w) for i, j, w in corners if np.isfinite(self.seconds[i, j])]
+        if len(have) == 4:
+            return float(sum(w * self.seconds[i, j] for i, j, w in have))
+        # A cell cut by the diagonal kv_len = q_len has unmeasured corners (no task has fewer keys than rows).  Two
+        # estimates from the measured ones, weights renormalised: their seconds (too high where they hold several
+        # times the task's work: long tasks on a coarse grid), and their seconds PER FLOP times the task's own flops
+        # (too high where a fixed cost dominates: short tasks).  Each errs upwards in its own regime; the smaller is
+        # taken.
+        tot = sum(w for _, _, w in have)
+        if not have:
             raise ValueError("no measured grid point around the task")
-        return float(sum(w * self.seconds[i, j] for i, j, w in corners if np.isfinite(self.seconds[i, j])) / tot)
+        if tot <= 0:  # the task sits on unmeasured corners only: the measured corners of the cell, equally
+            have, tot = [(i, j, 1.0) for i, j, _ in have], float(len(have))
+        fl = lambda i, j: task_flops(int(self.q_axis[i]), int(self.kv_axis[j]), self.n_q_heads, self.head_dim, self.backward)
+        by_seconds = sum(w * self.seconds[i, j] for i, j, w in have) / tot
+        per_flop = sum(w * self.seconds[i, j] / fl(i, j) for i, j, w in have) / tot
+        return float(min(by_seconds, per_flop * task_flops(q_len, kv_len, self.n_q_heads, self.head_dim, self.backward)))
 
     # ---- storage (JSON text)
     def to_json(self) -> str:

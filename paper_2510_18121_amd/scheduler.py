@@ -7,8 +7,12 @@ against the document's first q_pos + q_len tokens).  The scheduler moves Items, 
 above the mean load to servers below it, each time taking the candidate with the most FLOPs moved per byte sent,
 until every server is within eps of the mean or no move is worth its bytes.
 
-Work is counted in causal (query, key) pairs, exactly (workloads.task_pairs); FLOPs are a constant multiple.
-The cost function works on the paper's continuous form n_q (2 n_kv - n_q).
+An Item's load is priced either by its causal (query, key) pairs, exactly (workloads.task_pairs; FLOPs are a
+constant multiple), or - as in the paper, whose scheduler takes its costs from the Profiler - by the seconds a
+measured `profiler.LatencyGrid` predicts for its CA-task; pairs are the fallback without a grid.  Below the kernel's
+saturation region (short shards, short contexts) time is far from proportional to pairs, and only the grid sees that.
+The cost function works on the paper's continuous form n_q (2 n_kv - n_q).  Items here are contiguous; Appendix B's
+head-tail Items (a piece from the front of a document paired with its mirror image from the back) are not built.
 """
 from __future__ import annotations
 
@@ -64,19 +68,6 @@ def min_comm(alpha: float, L_q: float, L_kv: float, size_q: float, size_kv: floa
     return n_q, n_kv, comm_bytes(n_q, n_kv, size_q, size_kv)
 
 
-def min_comm_head_tail(alpha: float, L_q: float, L_kv: float, L_doc: float, size_q: float, size_kv: float):
-    """Appendix B, head-tail variant: an Item holds the document's tokens i..j from the front and the mirrored
-    tokens from the back; n_kv is the context of the head half.  The bytes grow with n_q, so the smallest
-    feasible n_q is optimal."""
-    if not (0.0 < alpha <= 1.0):
-        raise ValueError("alpha must be in (0, 1]")
-    beta = size_kv / size_q
-    c = alpha * shard_work(L_q, L_kv)
-    n_q = L_kv - math.sqrt(max(0.0, L_kv * L_kv - c))
-    v = L_doc * size_kv + 0.5 * size_q * (n_q * (2.0 + beta) - beta * c / n_q)
-    return n_q, v
-
-
 # ------------------------------------------------------------------------------------------- scheduler
 @dataclass
 class Item:
@@ -99,6 +90,14 @@ class Item:
         return W.task_pairs(self.q_pos, self.q_len)
 
 
+def item_cost(item: "Item", grid=None) -> float:
+    """Load of an Item: the seconds the latency grid predicts for its CA-task (Section 4.2, "Profiler"), or, without
+    a grid, its exact pair count."""
+    if grid is None:
+        return float(item.pairs)
+    return float(grid.predict(item.q_len, item.kv_len))
+
+
 @dataclass
 class Schedule:
     """Result of `schedule`: which Items every attention server computes, and what moving them cost."""
@@ -106,23 +105,27 @@ class Schedule:
     servers: list                      # per server: list of Items it computes
     moved_bytes: float = 0.0           # by the cost model (every move pays for its queries and its whole context)
     moves: list = field(default_factory=list)   # (source, destination, Item moved, bytes)
+    grid: object = None                # the LatencyGrid the loads were priced with, or None for pair counts
 
-    def loads(self):
-        """Per-server load in (query, key) pairs."""
-        return [sum(it.pairs for it in s) for s in self.servers]
+    def loads(self, grid="own"):
+        """Per-server load: predicted seconds under `grid` (default: the grid the schedule was made with), pairs
+        when that is None."""
+        g = self.grid if isinstance(grid, str) else grid
+        return [sum(item_cost(it, g) for it in s) for s in self.servers]
 
-    def imbalance(self) -> float:
+    def imbalance(self, grid="own") -> float:
         """max load / mean load."""
-        ld = self.loads()
+        ld = self.loads(grid)
         mean = sum(ld) / len(ld)
         return max(ld) / mean if mean > 0 else 1.0
 
 
-def _cut(item: Item, want_pairs: float, size_q: float, size_kv: float, block: int):
-    """The sub-shard of `item` of about want_pairs pairs that Appendix B's cost function prefers, on a grid of
-    `block` rows: returns (moved Item, remaining Items, modelled bytes)."""
+def _cut(item: Item, alpha: float, size_q: float, size_kv: float, block: int):
+    """The sub-shard of `item` that carries about the fraction alpha of its work and that Appendix B's cost function
+    prefers, on a grid of `block` rows: returns (moved Item, remaining Items, modelled bytes)."""
     L_q, L_kv = item.q_len, item.kv_len
-    alpha = min(1.0, want_pairs / item.pairs)
+    alpha = min(1.0, alpha)
+    want_pairs = alpha * item.pairs
     n_q, n_kv, _ = min_comm(alpha, L_q, L_kv, size_q, size_kv)
     n = int(round(n_q / block)) * block
     n = max(block, min(n, (L_q // block) * block if L_q >= block else L_q))
@@ -146,21 +149,26 @@ def _cut(item: Item, want_pairs: float, size_q: float, size_kv: float, block: in
 
 
 def schedule(items, n_servers: int, size_q: float, size_kv: float, eps: float = 0.05, min_gain: float = 0.0,
-             block: int = 16, max_moves: int = 100000) -> Schedule:
+             block: int = 16, max_moves: int = 100000, grid=None) -> Schedule:
     """Section 4.2, steps 1-3.
 
     items: Items, each on its home server.  size_q / size_kv: bytes per query token and per key-value token.
-    eps: tolerance on a server's load relative to the mean.  min_gain: a move must carry at least this many pairs
-    per byte (the paper's "small threshold" on the priority score E).  block: granularity of cuts in rows."""
+    eps: tolerance on a server's load relative to the mean.  min_gain: a move must carry at least this much load
+    per byte (the paper's "small threshold" on the priority score E; in pairs per byte, or seconds per byte with a
+    grid).  block: granularity of cuts in rows.  grid: a `profiler.LatencyGrid`; loads are then the predicted seconds
+    of the Items' CA-tasks (the paper's Profiler), otherwise exact pair counts.  A cut takes the fraction of the
+    Item's WORK (Appendix B works in flops) that equals the wanted fraction of its load; the pieces are then priced
+    anew, so the books stay exact in either unit."""
     servers = [[] for _ in range(n_servers)]
     for it in items:
         servers[it.home].append(it)
-    sch = Schedule(servers)
-    total = sum(it.pairs for it in items)
+    sch = Schedule(servers, grid=grid)
+    cost = lambda it: item_cost(it, grid)
+    load = sch.loads()
+    total = sum(load)
     mean = total / n_servers
     if total == 0:
         return sch
-    load = sch.loads()
     for _ in range(max_moves):
         # step 3 (checked first): every server within eps of the mean load
         if all(abs(x - mean) <= eps * mean for x in load):
@@ -170,35 +178,38 @@ def schedule(items, n_servers: int, size_q: float, size_kv: float, eps: float = 
         progressed = False
         for d in deficits:
             need = mean - load[d]
-            # step 2: the candidate with the most work moved per byte
+            # step 2: the candidate with the most load moved per byte
             best = None
             for s in range(n_servers):
                 surplus = load[s] - mean
                 if s == d or surplus <= 0:
                     continue
                 for idx, it in enumerate(servers[s]):
-                    df = min(it.pairs, surplus, need)
+                    f_item = cost(it)
+                    df = min(f_item, surplus, need)
                     if df <= 0:
                         continue
-                    if df >= it.pairs:
+                    if df >= f_item:
                         v = comm_bytes(it.q_len, it.kv_len, size_q, size_kv)
                     else:
-                        v = min_comm(df / it.pairs, it.q_len, it.kv_len, size_q, size_kv)[2]
+                        v = min_comm(df / f_item, it.q_len, it.kv_len, size_q, size_kv)[2]
                     e = df / v
                     if best is None or e > best[0]:
-                        best = (e, s, idx, df)
+                        best = (e, s, idx, df, f_item)
             if best is None or best[0] < min_gain:
                 continue
-            e, s, idx, df = best
+            e, s, idx, df, f_item = best
             it = servers[s].pop(idx)
-            if df >= it.pairs or it.q_len <= block:
+            if df >= f_item or it.q_len <= block:
                 moved, rest, v = it, [], comm_bytes(it.q_len, it.kv_len, size_q, size_kv)
             else:
-                moved, rest, v = _cut(it, df, size_q, size_kv, block)
+                moved, rest, v = _cut(it, df / f_item, size_q, size_kv, block)
             servers[s].extend(rest)
             servers[d].append(Item(moved.doc, moved.q_pos, moved.q_len, moved.home))
-            load[s] -= moved.pairs
-            load[d] += moved.pairs
+            load[s] += sum(cost(r) for r in rest) - f_item
+            load[d] += cost(moved)
+            if grid is not None:  # predicted times of pieces need not add up to the whole Item's
+                mean = sum(load) / n_servers
             sch.moved_bytes += v
             sch.moves.append((s, d, moved, v))
             progressed = True
@@ -263,22 +274,31 @@ def main():
     ap.add_argument("--workload", type=int, default=3)
     ap.add_argument("--servers", type=int, default=8)
     ap.add_argument("--eps", default="inf,0.2,0.1,0.05,0.02,0.01")
+    ap.add_argument("--grid", action="store_true",
+                    help="measure a latency grid first (Section 4.2, Profiler) and balance predicted seconds "
+                         "instead of pair counts")
     args = ap.parse_args()
     b = W.config(args.workload)
     size_q = b.n_q_heads * b.head_dim * 2          # bf16 query token
     size_kv = 2 * b.n_kv_heads * b.head_dim * 2    # bf16 key + value token
     items = items_from_batch(b, args.servers)
+    grid = None
+    if args.grid:
+        from .profiler import measure_grid
+        grid = measure_grid([16, 64, 256, 1024, 4096, 16384], [128, 512, 2048, 8192, 32768, 131072], b.n_q_heads,
+                            b.n_kv_heads, b.head_dim, steps=3, warmup=1)
     for e in args.eps.split(","):
         eps = float(e)
-        sch = Schedule([[it for it in items if it.home == s] for s in range(args.servers)]) if math.isinf(eps) \
-            else schedule(items, args.servers, size_q, size_kv, eps=eps)
+        sch = Schedule([[it for it in items if it.home == s] for s in range(args.servers)], grid=grid) \
+            if math.isinf(eps) else schedule(items, args.servers, size_q, size_kv, eps=eps, grid=grid)
         ms = []
         for s, srv in enumerate(sch.servers):
             sub, _, _ = server_batch(b, srv, name=f"server{s}")
             ms.append(time_batch(sub, steps=3, warmup=1))
-        ld = sch.loads()
         print(json.dumps({"eps": e, "servers": args.servers, "workload": b.name, "moves": len(sch.moves),
+                          "priced_by": "latency grid (s)" if grid is not None else "pairs",
                           "modelled_MB_moved": sch.moved_bytes / 1e6, "load_max_over_mean": sch.imbalance(),
+                          "pairs_max_over_mean": sch.imbalance(grid=None),
                           "server_ms": [round(x, 2) for x in ms], "time_max_over_mean": max(ms) / (sum(ms) / len(ms)),
                           "slowest_server_ms": max(ms), "sum_ms": sum(ms)}), flush=True)
 

@@ -58,6 +58,17 @@ def test_cells_cut_by_the_diagonal_use_their_measured_corners_only():
         g.predict(500, 400)
 
 
+def test_long_task_on_the_diagonal_of_a_coarse_grid_is_priced_by_its_own_work():
+    # fixed cost + work / rate; the whole-document task (q = kv = 16384) sits in a cell whose measured corners hold
+    # up to seven times its work: interpolating their seconds would overprice it several times over
+    f = lambda q, kv: 40e-6 + task_flops(q, kv, 8, 128) / 8e14
+    g = LatencyGrid([1024, 4096, 16384], [1024, 8192, 65536],
+                    [[f(q, kv) if kv >= q else np.nan for kv in (1024, 8192, 65536)] for q in (1024, 4096, 16384)], 8, 128,
+                    saturation_tolerance=-1.0)
+    assert g.predict(16384, 16384) == pytest.approx(f(16384, 16384), rel=0.1)
+    assert g.predict(4096, 4096) == pytest.approx(f(4096, 4096), rel=0.15)
+
+
 def test_json_round_trip():
     g = _grid(lambda q, kv: 1e-4 + 1e-9 * q * kv)
     h = LatencyGrid.from_json(g.to_json())

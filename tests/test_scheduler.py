@@ -55,19 +55,6 @@ def test_whole_item_and_bounds():
         S.min_comm(0.0, 10, 10, 1, 1)
 
 
-def test_head_tail_variant_takes_the_smallest_shard():
-    alpha, L_q, L_kv, L_doc, sq, skv = 0.25, 2048.0, 6000.0, 12000.0, 4.0, 2.0
-    n_q, v = S.min_comm_head_tail(alpha, L_q, L_kv, L_doc, sq, skv)
-    assert n_q == pytest.approx(L_kv - math.sqrt(L_kv ** 2 - alpha * S.shard_work(L_q, L_kv)))
-    # Comm(n_q, n_kv) = n_q size_q + (L_doc - (n_kv - n_q)) size_kv at n_kv = L_kv
-    assert v == pytest.approx(n_q * sq + (L_doc - (L_kv - n_q)) * skv)
-    # and any larger feasible n_q costs more
-    for m in (1.1, 1.5, 2.0):
-        n2 = n_q * m
-        nkv2 = S.n_kv_for(alpha, L_q, L_kv, n2)
-        assert n2 * sq + (L_doc - (nkv2 - n2)) * skv > v
-
-
 def _covered(sch, items):
     """Per document, the multiset of query positions computed somewhere."""
     got, want = {}, {}
@@ -142,3 +129,46 @@ def test_server_batch_gathers_the_right_rows():
         assert sub.pairs() == sum(it.pairs for it in srv)
         seen.extend(qrows.tolist())
     assert sorted(seen) == list(range(b.total_q))
+
+
+def _toy_grid():
+    """A latency grid with the shape the measured ones have: a fixed cost per task plus time proportional to the
+    work, so short shards are far dearer per pair than long ones."""
+    from paper_2510_18121_amd.profiler import LatencyGrid, task_flops
+    q_axis, kv_axis = [16, 64, 256, 1024, 4096, 16384], [16, 128, 1024, 8192, 65536]
+    sec = np.full((len(q_axis), len(kv_axis)), np.nan)
+    for i, q in enumerate(q_axis):
+        for j, kv in enumerate(kv_axis):
+            if kv >= q:
+                sec[i, j] = 40e-6 + task_flops(q, kv, 8, 128) / 800e12
+    return LatencyGrid(q_axis, kv_axis, sec, 8, 128)
+
+
+def test_grid_priced_schedule_balances_predicted_time_where_pairs_misprice_it():
+    """Sixteen-row tasks next to 16K-row tasks (Section 4.2: the scheduler's costs come from the Profiler).  By pair
+    count the server with the tiny tasks looks idle; by predicted time it is the busiest.  Balancing pairs leaves the
+    predicted times unbalanced; balancing with the grid evens them out."""
+    g = _toy_grid()
+    tiny = [S.Item(doc=i, q_pos=112, q_len=16, home=0) for i in range(600)]      # 600 x (40 us + a little)
+    big = [S.Item(doc=1000 + i, q_pos=0, q_len=16384, home=1) for i in range(2)]
+    items = tiny + big
+    by_pairs = S.schedule(items, 2, 8192.0, 4096.0, eps=0.02)
+    by_time = S.schedule(items, 2, 8192.0, 4096.0, eps=0.02, grid=g)
+    assert by_pairs.imbalance() <= 1.03                 # balanced in its own unit ...
+    assert by_pairs.imbalance(grid=g) > 1.25            # ... but not in predicted seconds
+    assert by_time.imbalance() <= 1.03 and by_time.grid is g
+    assert by_time.imbalance(grid=g) <= 1.03
+    # the first move goes opposite ways: by pairs the long documents' server is overloaded, by time the tiny tasks'
+    assert by_pairs.moves[0][0] == 1 and by_time.moves[0][0] == 0
+    # nothing is lost or duplicated either way
+    for sch in (by_pairs, by_time):
+        assert sum(it.pairs for srv in sch.servers for it in srv) == sum(it.pairs for it in items)
+
+
+def test_grid_priced_loads_are_the_sum_of_predictions():
+    g = _toy_grid()
+    items = [S.Item(0, 0, 4096, 0), S.Item(0, 4096, 4096, 0), S.Item(1, 0, 300, 1)]
+    sch = S.schedule(items, 2, 8192.0, 4096.0, eps=10.0, grid=g)   # tolerance so wide that nothing moves
+    assert not sch.moves
+    assert sch.loads() == pytest.approx([g.predict(4096, 4096) + g.predict(4096, 8192), g.predict(300, 300)])
+    assert sch.loads(grid=None) == [W.task_pairs(0, 4096) + W.task_pairs(4096, 4096), W.task_pairs(0, 300)]
