@@ -142,16 +142,25 @@ def time_batch(batch, steps: int = 5, warmup: int = 2, backward: bool = True):
 
 
 def measure_grid(q_axis, kv_axis, hq: int = 32, hkv: int = 8, d: int = 128, backward: bool = True,
-                 steps: int = 5, warmup: int = 2) -> LatencyGrid:
-    """Times a single task (one document of kv_len tokens, its last q_len tokens as the query shard) at every
-    grid point with kv_len >= q_len."""
+                 steps: int = 5, warmup: int = 2, fill_tokens: int = 0, max_kv_rows: int = 1 << 21) -> LatencyGrid:
+    """Times a task (one document of kv_len tokens, its last q_len tokens as the query shard) at every grid point with
+    kv_len >= q_len.
+
+    fill_tokens = 0: the task alone on the GPU (what a single small call costs; a lone task cannot fill 256 CUs).
+    fill_tokens > 0: the task's cost INSIDE a fused call, which is what an attention server runs and what the paper's
+    own kernel measurement does (Section 3.3: chunks packed with equal shards): a batch of n copies of the task, each
+    with a document of its own, n = fill_tokens / q_len (capped so that the copies' KV stays below max_kv_rows rows),
+    timed as one call and divided by n."""
     sec = np.full((len(q_axis), len(kv_axis)), np.nan)
     for i, ql in enumerate(q_axis):
         for j, kl in enumerate(kv_axis):
             if kl < ql:
                 continue
-            b = W.custom([int(kl)], [(0, int(kl - ql), int(ql))], hq, hkv, d, seed=11)
-            sec[i, j] = time_batch(b, steps, warmup, backward) * 1e-3
+            n = 1
+            if fill_tokens > 0:
+                n = max(1, min(int(fill_tokens) // int(ql), int(max_kv_rows) // int(kl)))
+            b = W.custom([int(kl)] * n, [(t, int(kl - ql), int(ql)) for t in range(n)], hq, hkv, d, seed=11)
+            sec[i, j] = time_batch(b, steps, warmup, backward) * 1e-3 / n
     return LatencyGrid(np.asarray(q_axis), np.asarray(kv_axis), sec, hq, d, backward)
 
 
@@ -164,10 +173,12 @@ def main():
     ap.add_argument("--heads", default="32,8")
     ap.add_argument("--forward-only", action="store_true")
     ap.add_argument("--json", action="store_true", help="print the grid as one JSON line (LatencyGrid.from_json reads it)")
+    ap.add_argument("--fill-tokens", type=int, default=0,
+                    help="time every task inside a fused call of this many query tokens of equal tasks (0: alone)")
     args = ap.parse_args()
     hq, hkv = (int(x) for x in args.heads.split(","))
     g = measure_grid([int(x) for x in args.q.split(",")], [int(x) for x in args.kv.split(",")], hq, hkv, 128,
-                     backward=not args.forward_only)
+                     backward=not args.forward_only, fill_tokens=args.fill_tokens)
     if args.json:
         print(g.to_json())
         return

@@ -277,6 +277,9 @@ def main():
     ap.add_argument("--grid", action="store_true",
                     help="measure a latency grid first (Section 4.2, Profiler) and balance predicted seconds "
                          "instead of pair counts")
+    ap.add_argument("--fill-tokens", type=int, default=32768,
+                    help="with --grid: every grid point is timed inside a fused call of this many query tokens of "
+                         "equal tasks (0: each task alone on the GPU)")
     args = ap.parse_args()
     b = W.config(args.workload)
     size_q = b.n_q_heads * b.head_dim * 2          # bf16 query token
@@ -286,7 +289,7 @@ def main():
     if args.grid:
         from .profiler import measure_grid
         grid = measure_grid([16, 64, 256, 1024, 4096, 16384], [128, 512, 2048, 8192, 32768, 131072], b.n_q_heads,
-                            b.n_kv_heads, b.head_dim, steps=3, warmup=1)
+                            b.n_kv_heads, b.head_dim, steps=3, warmup=1, fill_tokens=args.fill_tokens)
     for e in args.eps.split(","):
         eps = float(e)
         sch = Schedule([[it for it in items if it.home == s] for s in range(args.servers)], grid=grid) \
