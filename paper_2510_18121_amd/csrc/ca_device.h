@@ -244,6 +244,22 @@ __device__ __forceinline__ float exp2_fma_pinned(float x, float c, float g) {
   asm volatile("v_fma_f32 %0, %1, %2, -%3\n\tv_exp_f32 %0, %0" : "=v"(r) : "v"(x), "v"(c), "v"(g));
   return r;
 }
+// x = exp2(x * c - g) in place (the register of x is reused, so a register tuple exponentiated element by element
+// stays where it is), pinned likewise
+__device__ __forceinline__ void exp2_fma_inplace_pinned(float &x, float c, float g) {
+  asm volatile("v_fma_f32 %0, %0, %1, -%2\n\tv_exp_f32 %0, %0" : "+v"(x) : "v"(c), "v"(g));
+}
+// the same with sum += prev in between.  prev may be the result of the transcendental issued directly before this
+// statement: the multiply-add stands between the two.
+__device__ __forceinline__ void exp2_fma_add_inplace_pinned(float &x, float c, float g, float &sum, float prev) {
+  asm volatile("v_fma_f32 %0, %0, %2, -%3\n\tv_add_f32 %1, %1, %4\n\tv_exp_f32 %0, %0"
+               : "+v"(x), "+v"(sum)
+               : "v"(c), "v"(g), "v"(prev));
+}
+// sum += prev where prev may be the result of a transcendental issued directly before (one wait state supplied)
+__device__ __forceinline__ void add_after_trans_pinned(float &sum, float prev) {
+  asm volatile("s_nop 0\n\tv_add_f32 %0, %0, %1" : "+v"(sum) : "v"(prev));
+}
 __device__ __forceinline__ void pin(int &v) { asm volatile("" : "+v"(v)); }
 
 // wait until at most n of this wave's vector-memory loads are outstanding (n <= 63)

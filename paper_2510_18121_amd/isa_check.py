@@ -1,12 +1,12 @@
 """Static checks of the generated gfx950 instruction stream for the hazards the hand-written assembly must respect.
 
-Parts of the kernels are inline assembly that the compiler does not look into (the score MFMAs of the dK/dV kernel with
-architectural destination tuples; exponentials, conversions and packs pinned to their MFMA slots), so the wait states
+Parts of the kernels are inline assembly that the compiler does not look into (the score MFMAs of the dK/dV and
+forward kernels with architectural destination tuples; exponentials, conversions and packs pinned to their MFMA slots), so the wait states
 the compiler would otherwise insert are the author's responsibility.  This module compiles a kernel source to assembly
 and verifies, instruction by instruction:
 
-1. MFMA chains (`check_mfma_chains`, for the dK/dV kernel, whose score MFMAs are assembly; elsewhere MFMAs are
-   compiler builtins and the compiler supplies the wait states itself): from the first MFMA that writes an architectural tuple with a fresh C operand to
+1. MFMA chains (`check_mfma_chains`, for the dK/dV kernel and the forward kernel, whose score MFMAs are assembly;
+   elsewhere MFMAs are compiler builtins and the compiler supplies the wait states itself): from the first MFMA that writes an architectural tuple with a fresh C operand to
    the end of its chain (an `s_nop 11`, or the `; chain end` marker), nothing but MFMAs touches the chain's registers
    and no control flow intervenes; after a `; chain end` marker (no wait states by design) no non-MFMA instruction
    touches those registers for the next 16 issue cycles at least.
@@ -155,7 +155,7 @@ def main():
     status = 0
     for src in ("ca_bwd.hip", "ca_fwd.hip"):
         asm = compile_to_asm(src)
-        for body in kernel_bodies(asm, "ca_bwd_dkv_kernel"):
+        for body in kernel_bodies(asm, "ca_bwd_dkv_kernel") + kernel_bodies(asm, "ca_fwd_kernel"):
             n, marks, bad = check_mfma_chains(body)
             print(f"{src}: {body.split(':')[0]}: {n} hand-written MFMA chains, {marks} chain-end markers, "
                   f"{len(bad)} findings")

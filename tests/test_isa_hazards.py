@@ -32,9 +32,19 @@ def test_no_vector_instruction_reads_a_transcendental_in_the_next_slot(bwd_asm):
     assert not bad, bad
 
 
-def test_forward_kernel_transcendentals():
-    n, bad = C.check_trans_use(C.compile_to_asm("ca_fwd.hip"))
+def test_forward_kernel_transcendentals_and_chains():
+    asm = C.compile_to_asm("ca_fwd.hip")
+    n, bad = C.check_trans_use(asm)
     assert n > 50 and not bad, bad
+    bodies = C.kernel_bodies(asm, "ca_fwd_kernel")
+    assert len(bodies) == 2  # head_dim 128 and 64
+    for body in bodies:
+        # score chains of the pipelined steps, of the prologue and of the diagonal path, every one ended by wait states
+        n, marks, bad = C.check_mfma_chains(body)
+        assert n >= 6 and marks == 0
+        assert not bad, bad
+        # the pipelined loop keeps everything in registers
+        assert "scratch_" not in body
 
 
 M = "v_mfma_f32_32x32x16_bf16"
