@@ -204,9 +204,10 @@ def main():
         with probe_clocks:
             sustained = mfma_rate.sustained_tflops("normal", 0, 1, device=dev)[-1]
         sustained_side = mfma_rate.sustained_tflops("normal", 1, 1, device=dev)[-1]
-        # the other two kernels run two waves per SIMD: the dQ kernel's side work is about level 1, the forward's level 2
+        # the dQ kernel runs two waves per SIMD with side work of about level 1; the forward kernel one wave per SIMD
+        # with side work of about level 2 (an exponential per MFMA)
         sustained_dq = mfma_rate.sustained_tflops("normal", 1, 2, device=dev)[-1]
-        sustained_fwd = mfma_rate.sustained_tflops("normal", 2, 2, device=dev)[-1]
+        sustained_fwd = mfma_rate.sustained_tflops("normal", 2, 1, device=dev)[-1]
     if args.calibration_copy_mib > 0:
         src = torch.empty(args.calibration_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(3)
         dst = torch.empty_like(src)
@@ -258,7 +259,7 @@ def main():
             "during_probe": probe_clocks.summary(), "with_side_work_tflops": sustained_side,
             "frac_with_side_work": bwd_main_tflops / sustained_side,
             "other_kernels": {
-                "ca_fwd_kernel": {"executed_tflops": fwd_tflops, "stream_two_waves_side_work_2_tflops": sustained_fwd,
+                "ca_fwd_kernel": {"executed_tflops": fwd_tflops, "stream_one_wave_side_work_2_tflops": sustained_fwd,
                                   "frac": fwd_tflops / sustained_fwd},
                 "ca_bwd_dq_kernel": {"executed_tflops": dq_tflops, "stream_two_waves_side_work_1_tflops": sustained_dq,
                                      "frac": dq_tflops / sustained_dq}},
