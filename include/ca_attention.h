@@ -233,7 +233,8 @@ const char *ca_last_error(void); /* thread-local detail of the last failing call
  * ca_plan_info fills `out[0..n)` with, in order: q_tile_rows, n_q_tiles, n_fwd_units, kv_tile_rows,
  * n_bwd_units, fwd_kv_step, padded_rows, sum over forward units of KV steps, sum over backward units of
  * (q blocks x heads) steps, bwd_q_block_rows, slot_align (a document's rows are padded to this many slots),
- * heads_packed (query heads per head-packed forward unit).  n_q_tiles counts the full 256-slot tiles.
+ * heads_packed (query heads per head-packed forward unit), n_bwd_workgroups (workgroups of the dK/dV kernel: short
+ * backward units are chained, see below).  n_q_tiles counts the full 256-slot tiles.
  * Returns the number of values available.
  */
 int ca_plan_info(const ca_plan_t *plan, int64_t *out, int n);
@@ -244,9 +245,12 @@ int ca_plan_info(const ca_plan_t *plan, int64_t *out, int n);
  *                             heads per unit hp}: a unit is one workgroup of the forward and dQ kernels and
  *                             covers 256 / hp slots of hp consecutive query heads of one KV group; hp = 1 for the
  *                             full 256-slot tiles of a document, heads_packed for the slots left over
- *  bwd  : [n_bwd_units][7] = {first slot of first q block, slots end, first slot from which every slot sees the
+ *  bwd  : [n_bwd_units][9] = {first slot of first q block, slots end, first slot from which every slot sees the
  *                             whole tile, packed KV row of the tile's first key, valid keys in tile, document
- *                             position of the tile's first key, KV head}
+ *                             position of the tile's first key, KV head, follow, count}.  The first
+ *                             n_bwd_workgroups units are one workgroup of the dK/dV kernel each (longest first; unit
+ *                             index modulo n_kv_heads = KV head); such a unit has count >= 1, and its workgroup goes
+ *                             on with the count - 1 units stored from index `follow` on (same KV head, count 0)
  */
 int64_t ca_plan_rows(const ca_plan_t *plan, int32_t *rows, int32_t *pos);
 int64_t ca_plan_fwd_units(const ca_plan_t *plan, int32_t *units);

@@ -111,7 +111,8 @@ class Plan:
     """Owner of a ca_plan_t*."""
 
     INFO_KEYS = ("q_tile_rows", "n_q_tiles", "n_fwd_units", "kv_tile_rows", "n_bwd_units", "fwd_kv_step",
-                 "padded_rows", "fwd_steps", "bwd_steps", "bwd_q_block_rows", "slot_align", "heads_packed")
+                 "padded_rows", "fwd_steps", "bwd_steps", "bwd_q_block_rows", "slot_align", "heads_packed",
+                 "n_bwd_workgroups")
 
     def __init__(self, handle, batch):
         self.handle = ctypes.c_void_p(handle)
@@ -145,7 +146,7 @@ class Plan:
 
     def bwd_units(self):
         n = lib().ca_plan_bwd_units(self.handle, None)
-        u = np.zeros((n, 7), np.int32)
+        u = np.zeros((n, 9), np.int32)
         lib().ca_plan_bwd_units(self.handle, u.ctypes.data)
         return u
 

@@ -283,16 +283,15 @@ struct DkvSmem {
   static constexpr int TOTAL = NST * STAGE;
 };
 
-template <int D>
-__global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__restrict__ units,
-                                                            const int32_t *__restrict__ slot_pos,
-                                                            const bf16_t *__restrict__ Qs, const bf16_t *__restrict__ K,
-                                                            const bf16_t *__restrict__ V, const bf16_t *__restrict__ dOs,
-                                                            const float *__restrict__ l2_slot,
-                                                            const float *__restrict__ delta_slot,
-                                                            bf16_t *__restrict__ dK, bf16_t *__restrict__ dV,
-                                                            int32_t *progress, int peer_stride, int Hq, int Hkv,
-                                                            int64_t padded, float scale) {
+template <int D, bool CHAIN>
+__device__ __forceinline__ void dkv_workgroup(const int me, const BwdUnit &first,
+                                              const BwdUnit *__restrict__ units, int n_single,
+                                              const int32_t *__restrict__ slot_pos, const bf16_t *__restrict__ Qs,
+                                              const bf16_t *__restrict__ K, const bf16_t *__restrict__ V,
+                                              const bf16_t *__restrict__ dOs, const float *__restrict__ l2_slot,
+                                              const float *__restrict__ delta_slot, bf16_t *__restrict__ dK,
+                                              bf16_t *__restrict__ dV, int32_t *progress, int peer_stride, int Hq,
+                                              int Hkv, int64_t padded, float scale) {
   using S = DkvSmem<D>;
   constexpr int NS = D / 16, NDB = D / 32, CH = D / 8, RPI = 64 / CH, NST = S::NST;
   constexpr int NLD = BWD_BQ / (4 * RPI);  // direct loads per wave per Q (or dO) tile
@@ -303,19 +302,54 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
   const uint32_t lds0 = (uint32_t)(uintptr_t)(CA_LDS char *)smem;  // LDS byte address of the dynamic segment
-  const BwdUnit u = units[blockIdx.x];
-  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, r = lane & 31;
+  // The workgroup's units, one after the other (all of one KV head).  The lane's indices are derived again for every
+  // unit (through an opaque copy, so that the compiler does not keep what follows from them in registers across the
+  // whole unit loop).  Two things are carried from a unit to the next:
+  //  - the Q/dO stream.  Short units that follow each other are mostly the KV tiles of one document under the same
+  //    query rows (a shard with a long context): the next unit walks the same (block, head) tiles.  If this unit
+  //    ends in the pipelined path, the prefetch cursor wraps round to the first tile instead of stopping at the last,
+  //    and the next unit finds its first tiles in the stages, in the state in which the pipelined path expects them:
+  //    no drain, no refill (`cont`).
+  //  - the next unit's K and V fragments, fetched into registers while this unit computes (`have_kv`).
+  int pblk = 0, ph = 0, pst = 0;
+  uint32_t pst_addr = lds0;  // LDS address of the stage being filled
+  const char *q_tile = nullptr, *do_tile = nullptr, *q_first = nullptr, *do_first = nullptr;
+  const float *aux_ptr = nullptr, *aux_first = nullptr;
+  int qoff[NS];  // natural fragment s of tile row r (second sub-block: + 32 rows)
+  int toff[2][NDB];
+  int auxo = 0, auxq = 0, stage = 0, qstage = 0;
+  bf16x8 kf[NS], vf[NS], kfn[NS], vfn[NS];
+  bool cont = false, have_kv = false;
+  // (unit descriptors are fetched two units ahead, so that no unit starts by waiting for its own)
+  // Workgroups of one unit and chains are two instances of this function (CHAIN), so that a unit that runs alone pays
+  // for none of this.
+  BwdUnit u = first;
+  const int count = CHAIN ? u.count : 1, follow = u.follow;
+  BwdUnit nu = units[count > 1 ? follow : me];
+  for (int ui = 0; ui < count; ++ui) {
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, g = lane >> 5, r = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int li = lane & 15, dh = (lane >> 4) & 1;
-  const int G = Hq / Hkv, hk = u.kv_head;
+  const int G = Hq / Hkv;
   const int kw0 = 32 * wave;
   const float c = scale * LOG2E;
+  const bool has_next = CHAIN && ui + 1 < count;
+  const BwdUnit nnu = units[ui + 2 < count ? follow + ui + 1 : me];
+  const int hk = u.kv_head;
   const int key_pos = u.key_pos0 + kw0 + r;  // document position of this lane's key
   const int n_blocks = (u.slot_end - u.slot_begin) / BWD_BQ;
   const int n_it = n_blocks * G;
   // Query blocks are walked from the last one backwards (below), so the blocks that lie entirely below the
   // diagonal of this KV tile come first: they take the pipelined path without mask.
   const int n_fast = ((u.slot_end - u.slot_full) / BWD_BQ) * G;
+  // the stream goes on into the next unit / the next unit's K and V are fetched ahead (the loads go out before the
+  // pipelined loop; the wait of its third step is the first that is certain to have seen all of them land.  Issued
+  // inside the loop, after its first wait, they would have longer to land, but the branch that takes costs every
+  // step of every unit more than it gains)
+  const bool wrap = has_next && n_it > 0 && n_fast == n_it && nu.slot_begin == u.slot_begin && nu.slot_end == u.slot_end;
+  const bool fetch_kv = has_next && n_fast >= 3;
 
   // ---- loads of one (q block, head): this wave fetches tile rows RPW*wave .. +RPW-1 of Q and of dO, plus one
   // 64-float auxiliary array.  Q and dO come from their slot-ordered copies [block][head][64][D], in which the tile
@@ -330,22 +364,14 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   // Prefetch cursor: (pblk, ph) is the next (query block, head of the group) to fetch.  Query blocks are walked
   // from the document's LAST block backwards: every KV tile of a document then starts at the same block, so the
   // workgroups that run side by side on an XCD (same KV head, neighbouring KV tiles) fetch the same Q/dO tiles
-  // at about the same time and share them in that XCD's L2.  Past the last block the cursor stays on it: every
-  // iteration issues the same number of loads, which keeps the s_waitcnt bookkeeping constant.
-  int pblk = n_blocks - 1, ph = 0, pst = 0;
-  uint32_t pst_addr = lds0;  // LDS address of the stage being filled
+  // at about the same time and share them in that XCD's L2.  Past the last block the cursor stays on it (or wraps,
+  // see above): every iteration issues the same number of loads, which keeps the s_waitcnt bookkeeping constant.
   const int64_t head_stride = BWD_BQ * D * 2;            // bytes between the tiles of consecutive heads of a block
   const int64_t block_stride = int64_t(Hq) * head_stride;  // ... of consecutive blocks, same head
-  const int64_t tile0 = (int64_t(u.slot_begin / BWD_BQ + pblk) * Hq + hk * G) * head_stride;
-  const char *q_tile = reinterpret_cast<const char *>(Qs) + tile0, *do_tile = reinterpret_cast<const char *>(dOs) + tile0;
   // the wave's auxiliary array: log2e*LSE (wave 0), -Delta (wave 1), slot positions (wave 2); wave 3's load goes to
   // a spare area, so that every wave issues the same number of loads, and brings the peers' progress counters (below)
   const int64_t aux_hstride = wave < 2 ? padded : 0;
   const int aux_bstep = wave == 3 ? 0 : BWD_BQ;
-  const float *aux_ptr = (wave == 0 ? l2_slot + int64_t(hk) * G * padded
-                          : wave == 1 ? delta_slot + int64_t(hk) * G * padded
-                                      : reinterpret_cast<const float *>(slot_pos)) +
-                         u.slot_begin + int64_t(pblk) * BWD_BQ + lane;
   // Convoy.  The workgroups of one KV head that run on one XCD (units peer_stride apart) walk the same Q/dO tiles
   // from the same last block; as long as they are within an L2's worth of steps of each other only the first
   // of them fetches a tile from beyond the L2.  Each workgroup publishes the number of steps it has taken; wave 3's
@@ -360,20 +386,31 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   constexpr int CONVOY = (1 << 20) / (2 * BWD_BQ * ROWB);  // 1 MB of Q/dO tiles (a quarter of an L2), in steps
   constexpr int CONVOY_REACH = 3 * CONVOY;                 // peers further behind than this are left alone
   constexpr int CONVOY_MIN_STEPS = (64 << 20) / (2 * BWD_BQ * ROWB);
-  const int n_units = int(gridDim.x);
-  if (wave == 3) {
-    const int me = int(blockIdx.x), grp = 32 * peer_stride;
-    const int pu = me - me % grp + me % peer_stride + peer_stride * lane;
-    const int32_t *pp = progress + n_units;  // a counter that stays 0: "not running"
-    if (lane < 32 && pu < n_units && pu != me) {
-      const BwdUnit o = units[pu];
-      if (o.slot_end == u.slot_end && o.kv_head == u.kv_head && o.slot_end > o.slot_begin) pp = progress + pu;
+  if (!cont) {
+    pblk = n_blocks - 1, ph = 0, pst = 0;
+    pst_addr = lds0;
+    const int64_t tile0 = (int64_t(u.slot_begin / BWD_BQ + pblk) * Hq + hk * G) * head_stride;
+    q_tile = reinterpret_cast<const char *>(Qs) + tile0, do_tile = reinterpret_cast<const char *>(dOs) + tile0;
+    aux_ptr = (wave == 0 ? l2_slot + int64_t(hk) * G * padded
+               : wave == 1 ? delta_slot + int64_t(hk) * G * padded
+                           : reinterpret_cast<const float *>(slot_pos)) +
+              u.slot_begin + int64_t(pblk) * BWD_BQ + lane;
+    // Only workgroups of a single unit have peers: those come first in the list, and their index is their unit's.
+    if (wave == 3) {
+      const int grp = 32 * peer_stride;
+      const int pu = me - me % grp + me % peer_stride + peer_stride * lane;
+      const int32_t *pp = progress + n_single;  // a counter that stays 0: "not running"
+      if (!CHAIN && lane < 32 && pu < n_single && pu != me) {
+        const BwdUnit o = units[pu];
+        if (o.slot_end == u.slot_end && o.kv_head == u.kv_head && o.slot_end > o.slot_begin) pp = progress + pu;
+      }
+      aux_ptr = reinterpret_cast<const float *>(pp);
     }
-    aux_ptr = reinterpret_cast<const float *>(pp);
+    q_first = q_tile, do_first = do_tile, aux_first = aux_ptr;
   }
-  int32_t *const my_progress = progress + blockIdx.x;
-  auto publish = [&](int steps) __attribute__((always_inline)) {  // call from wave 3 only
-    if (lane == 0) __hip_atomic_store(my_progress, steps, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  int32_t *const my_progress = progress + me;
+  auto publish = [&](int steps) __attribute__((always_inline)) {  // call from wave 3 only; chains have no peers
+    if (!CHAIN && lane == 0) __hip_atomic_store(my_progress, steps, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   };
   const uint32_t aux_lds = wave == 0 ? S::L2_OFF : wave == 1 ? S::DL_OFF : wave == 2 ? S::POS_OFF : S::SPARE_OFF;
   constexpr int LPI = 2 * NLD + 1;  // loads per wave per iteration
@@ -398,6 +435,10 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
       --pblk;
       q_tile -= (G - 1) * head_stride + block_stride, do_tile -= (G - 1) * head_stride + block_stride;
       aux_ptr -= (G - 1) * aux_hstride + aux_bstep;
+    } else if (wrap) {  // past the end: the next unit's first (block, head), which is this unit's
+      ph = 0;
+      pblk = n_blocks - 1;
+      q_tile = q_first, do_tile = do_first, aux_ptr = aux_first;
     }  // else: past the end, keep re-fetching the final (block, head)
   };
   auto issue_next = [&]() __attribute__((always_inline)) {
@@ -421,7 +462,7 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   constexpr int NB1 = NPOST;
   constexpr int LP1 = NB1;  // pieces of the newest block that are issued before the pipelined path takes over
 
-  if (n_it > 0) {
+  if (n_it > 0 && !cont) {
     issue_next();  // blocks 0 .. 3: four ahead; the last one is completed further down
     issue_next();
     issue_next();
@@ -431,25 +472,39 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
 
   // resident K, V fragments of the wave's 32 keys (B operands of S = Q K^T and dP = dO V^T).  Keys past the
   // document's last key are clamped; their positions exceed every query position, so they are masked.
-  bf16x8 kf[NS], vf[NS];
-  {
-    const int key = min(kw0 + r, u.n_valid - 1);
-    const size_t off = (size_t(u.kv_row + key) * Hkv + hk) * D + 8 * g;
+  auto kv_offset = [&](const BwdUnit &x) __attribute__((always_inline)) {
+    const int key = min(kw0 + r, x.n_valid - 1);
+    return (size_t(x.kv_row + key) * Hkv + hk) * D + 8 * g;
+  };
+  // (If they were fetched ahead, the previous unit has moved them into place at its end.)  All register loads are
+  // complete from here on, so the compiler places no vector-memory waits inside the loops (they would drain the
+  // direct-load queue every iteration).
+  if (!have_kv) {
+    const size_t off = kv_offset(u);
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       kf[s] = *reinterpret_cast<const bf16x8 *>(K + off + 16 * s);
       vf[s] = *reinterpret_cast<const bf16x8 *>(V + off + 16 * s);
     }
+    wait_vmcnt<0>();
+#pragma unroll
+    for (int s = 0; s < NS; ++s) pin_acc(kf[s]), pin_acc(vf[s]);
   }
-  int qoff[NS];  // natural fragment s of tile row r (second sub-block: + 32 rows)
+  if (!cont) {
 #pragma unroll
-  for (int s = 0; s < NS; ++s) qoff[s] = lds0 + tile_off<D>(r, 2 * s + g);
-  int toff[2][NDB];
+    for (int s = 0; s < NS; ++s) qoff[s] = lds0 + tile_off<D>(r, 2 * s + g);
 #pragma unroll
-  for (int h2 = 0; h2 < 2; ++h2)
+    for (int h2 = 0; h2 < 2; ++h2)
 #pragma unroll
-    for (int b = 0; b < NDB; ++b)
-      toff[h2][b] = lds0 + tile_off<D>(4 * g + (li >> 2) + 8 * h2, 4 * b + 2 * dh + ((li >> 1) & 1)) + 8 * (li & 1);
+      for (int b = 0; b < NDB; ++b)
+        toff[h2][b] = lds0 + tile_off<D>(4 * g + (li >> 2) + 8 * h2, 4 * b + 2 * dh + ((li >> 1) & 1)) + 8 * (li & 1);
+    // qoff / auxq (natural reads and row statistics of the score chain) and toff / auxo (transposed reads, row
+    // statistics of the vector work) are byte offsets into a stage, advanced once per block, so that every LDS read
+    // is (loop-carried register) + (immediate).  In the pipelined path the first pair runs one stage ahead of the
+    // second for part of the time.
+    auxo = lds0 + 16 * g, auxq = auxo;
+    stage = 0, qstage = 0;
+  }
 
   f32x16 acc_dk[NDB], acc_dv[NDB];
 #pragma unroll
@@ -457,12 +512,7 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc_dk[b][i] = 0.f, acc_dv[b][i] = 0.f;
 
-  // All register loads above are complete from here on, so the compiler places no vector-memory waits
-  // inside the loops (they would drain the direct-load queue every iteration).
-  wait_vmcnt<0>();
-#pragma unroll
-  for (int s = 0; s < NS; ++s) pin_acc(kf[s]), pin_acc(vf[s]);
-  barrier_nofence();
+  if (!cont) barrier_nofence();
 
   // ------------------------------------------------------------------------------------------------
   // Pipelined path for blocks entirely below the diagonal.  With one wave per SIMD nothing hides a latency except
@@ -483,12 +533,6 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
   // two blocks in flight.
   bf16x8 opq[PA], opd[PA];  // natural fragments, k-steps s .. s+PA-1 of the score chain in flight
   bf16x8 opb[2 * NDB];      // transposed fragments: [2b] = dO^T, [2b+1] = Q^T of column block b
-  // qoff / auxq (natural reads and row statistics of the score chain) and toff / auxo (transposed reads, row
-  // statistics of the vector work) are byte offsets into a stage, advanced once per block, so that every LDS read
-  // is (loop-carried register) + (immediate).  In the pipelined path the first pair runs one stage ahead of the
-  // second for part of the time.
-  int auxo = lds0 + 16 * g, auxq = auxo;
-  int stage = 0, qstage = 0;
   auto advance_q = [&]() __attribute__((always_inline)) {
     const int adv = qstage == NST - 1 ? -(NST - 1) * S::STAGE : S::STAGE;
     qstage = qstage == NST - 1 ? 0 : qstage + 1;
@@ -582,9 +626,12 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
       else mfma_settle(sw, dpw, ndt);
     };
 
-    // blocks 0 and 1 have landed (this wave's part); block 2 and the issued part of block 3 may be in flight
-    wait_vmcnt<LPI + LP1>();
-    barrier_nofence();
+    // blocks 0 and 1 have landed (this wave's part); block 2 and the issued part of block 3 may be in flight.
+    // (A continued stream is in that state already, for every wave: the previous unit's last barrier saw to it.)
+    if (!cont) {
+      wait_vmcnt<LPI + LP1>();
+      barrier_nofence();
+    }
 #pragma unroll
     for (int s = 0; s < PA; ++s) {
       opd[s] = lds_read8_at(S::DO_OFF + qoff[s]);
@@ -599,6 +646,14 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
     }
     load_l2(auxo);
     load_nd(auxq + 32 * 4);
+    if (fetch_kv) {
+      const size_t off = kv_offset(nu);
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        kfn[s] = *reinterpret_cast<const bf16x8 *>(K + off + 16 * s);
+        vfn[s] = *reinterpret_cast<const bf16x8 *>(V + off + 16 * s);
+      }
+    }
 
     for (; it < n_fast; ++it) {
       // wave 3: a peer's counter as of about three steps ago (the other waves read their own filler)
@@ -686,7 +741,7 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
     }
   }
 
-  if (n_it > 0) {  // complete the block whose first pieces were issued last
+  if (n_it > 0 && !wrap) {  // complete the block whose first pieces were issued last
 #pragma unroll
     for (int i = LP1; i < LPI; ++i) issue_piece(i);
   }
@@ -757,7 +812,15 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
     if (wave == 3) publish(it + 1);
   }
   if (wave == 3) publish(-1);  // finished: peers no longer wait for this workgroup
-  wait_vmcnt<0>();  // nothing may still be writing LDS when the workgroup ends
+  if (!wrap) wait_vmcnt<0>();  // nothing may still be writing LDS when the stream ends
+  // The next unit's K and V take their place now, before the stores: the wait for them that the compiler puts here
+  // waits for everything this wave has in flight, which at this point is a few stream loads issued a step ago.
+  if (fetch_kv) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) kf[s] = kfn[s], vf[s] = vfn[s];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) pin_acc(kf[s]), pin_acc(vf[s]);
+  }
 
   // ---- write dK (scaled) and dV of the wave's 32 keys
   if (kw0 + r < u.n_valid) {
@@ -774,6 +837,33 @@ __global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__res
         *reinterpret_cast<u32x2 *>(dV + off + 32 * b + 8 * q4) = wv;
       }
   }
+  // every wave is done with the LDS stages before a new stream refills them
+  if (has_next && !wrap) __syncthreads();
+  cont = wrap, have_kv = fetch_kv;
+  u = nu, nu = nnu;
+  }
+}
+
+// Units that run alone and chains of short units in one launch, so that the dispatcher hands them out longest first
+// whatever they are.
+template <int D>
+__global__ __launch_bounds__(256, 1) void ca_bwd_dkv_kernel(const BwdUnit *__restrict__ units, int n_single,
+                                                            const int32_t *__restrict__ slot_pos,
+                                                            const bf16_t *__restrict__ Qs, const bf16_t *__restrict__ K,
+                                                            const bf16_t *__restrict__ V, const bf16_t *__restrict__ dOs,
+                                                            const float *__restrict__ l2_slot,
+                                                            const float *__restrict__ delta_slot,
+                                                            bf16_t *__restrict__ dK, bf16_t *__restrict__ dV,
+                                                            int32_t *progress, int peer_stride, int Hq, int Hkv,
+                                                            int64_t padded, float scale) {
+  const int me = int(blockIdx.x);  // index of the workgroup = index of its first unit
+  const BwdUnit first = units[me];
+  if (first.count <= 1)
+    dkv_workgroup<D, false>(me, first, units, n_single, slot_pos, Qs, K, V, dOs, l2_slot, delta_slot, dK, dV, progress,
+                            peer_stride, Hq, Hkv, padded, scale);
+  else
+    dkv_workgroup<D, true>(me, first, units, n_single, slot_pos, Qs, K, V, dOs, l2_slot, delta_slot, dK, dV, progress,
+                           peer_stride, Hq, Hkv, padded, scale);
 }
 
 static void launch_fill(void *p, size_t bytes, hipStream_t st) {
@@ -814,7 +904,7 @@ static hipError_t launch_bwd_t(const ca_plan_t *p, const void *q, const void *k,
   }
   if (!p->q_covered) launch_fill(dq, q_elems * 2, st);
   if (padded > 0) {
-    const int n_progress = int(p->bwd_units.size()) + 64;
+    const int n_progress = p->bwd_workgroups + 64;
     const int64_t threads = std::max<int64_t>(padded * p->hq * (D / 8), n_progress);
     hipLaunchKernelGGL(ca_bwd_prep_kernel, dim3(unsigned((threads + 255) / 256)), dim3(256), 0, st, p->d_slot_row,
                        static_cast<const bf16_t *>(q), static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(d_o),
@@ -826,11 +916,10 @@ static hipError_t launch_bwd_t(const ca_plan_t *p, const void *q, const void *k,
     static std::atomic<bool> done[16];
     hipError_t e = set_smem(kern, DkvSmem<D>::TOTAL, p->device, done);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(unsigned(p->bwd_units.size())), dim3(256), DkvSmem<D>::TOTAL, st, p->d_bwd_units,
-                       p->d_slot_pos, q_sorted, static_cast<const bf16_t *>(k), static_cast<const bf16_t *>(v),
-                       do_sorted, l2_slot, delta_slot,
-                       static_cast<bf16_t *>(dk), static_cast<bf16_t *>(dv), progress, p->peer_stride, p->hq, p->hkv,
-                       padded, p->scale);
+    hipLaunchKernelGGL(kern, dim3(unsigned(p->bwd_workgroups)), dim3(256), DkvSmem<D>::TOTAL, st, p->d_bwd_units,
+                       p->bwd_single, p->d_slot_pos, q_sorted, static_cast<const bf16_t *>(k),
+                       static_cast<const bf16_t *>(v), do_sorted, l2_slot, delta_slot, static_cast<bf16_t *>(dk),
+                       static_cast<bf16_t *>(dv), progress, p->peer_stride, p->hq, p->hkv, padded, p->scale);
   }
   if (ev) (void)hipEventRecord(ev[2], st);
   if (!p->fwd_units.empty()) {

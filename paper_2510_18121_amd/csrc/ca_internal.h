@@ -37,6 +37,12 @@ struct BwdUnit {  // one (KV tile, KV head)
   int32_t n_valid;     // valid keys in the tile
   int32_t key_pos0;    // document position of the tile's first key
   int32_t kv_head;
+  // Chains.  The first n_bwd_workgroups units of the list are one workgroup each; a workgroup goes on with the
+  // `count - 1` units stored from index `follow` on (behind the workgroups' own units; same KV head, no longer than
+  // its first).  Long units run alone (count 1); short ones are chained, because what a unit costs beyond its steps
+  // (filling the pipeline, fetching K and V, draining) can then overlap with the steps of its neighbours.
+  int32_t follow;
+  int32_t count;  // units of this workgroup including this one; 0 in a unit that follows another
 };
 
 }  // namespace ca
@@ -52,6 +58,8 @@ struct ca_plan {
   std::vector<int32_t> slot_row, slot_pos;
   std::vector<ca::FwdUnit> fwd_units;
   std::vector<ca::BwdUnit> bwd_units;
+  int32_t bwd_workgroups = 0;  // workgroups of the dK/dV kernel: the leading units of bwd_units
+  int32_t bwd_single = 0;      // so many leading workgroups are units that run alone (only those pace each other)
   int64_t fwd_steps = 0, bwd_steps = 0;
   // workspace layout for backward: [Delta fp32 hq*padded_slots][log2e*LSE fp32 hq*padded_slots]
   int slot_align = ca::SLOT_ALIGN, heads_packed = 1;  // padding of a document's slots; hp of the packed units

@@ -203,15 +203,56 @@ void schedule(ca_plan_t *p) {
   std::stable_sort(btiles.begin(), btiles.end(), [](const BwdUnit &a, const BwdUnit &b) {
     return (a.slot_end - a.slot_begin) > (b.slot_end - b.slot_begin);
   });
-  p->bwd_units.reserve(btiles.size() * hkv);
   p->bwd_steps = 0;
-  for (auto &t : btiles)
-    for (int h = 0; h < hkv; ++h) {
-      BwdUnit u = t;
-      u.kv_head = h;
-      p->bwd_units.push_back(u);
-      p->bwd_steps += int64_t(u.slot_end - u.slot_begin) / BWD_BQ * g;
+  for (auto &t : btiles) p->bwd_steps += int64_t(t.slot_end - t.slot_begin) / BWD_BQ * g * hkv;
+  {
+    // Chains of the dK/dV kernel: consecutive KV tiles of the sorted list (equal or similar cost; the tiles of one
+    // document under the same query rows are neighbours in it) whose units are short - at most CHAIN_UNIT_STEPS
+    // steps each: what chaining saves per unit is a few steps' worth - go to one workgroup per KV head, until the
+    // chain holds about 1/8 of a CU's share of the kernel's steps (so that at least 8 workgroups per CU remain for the
+    // dispatcher to balance with), at most CHAIN_STEPS_MAX steps and at most CHAIN_UNITS_MAX units.
+    constexpr int64_t N_CU = 256, CHAIN_UNIT_STEPS = 16, CHAIN_STEPS_MAX = 128, CHAIN_UNITS_MAX = 16;
+    const int64_t target = std::max<int64_t>(1, std::min<int64_t>(CHAIN_STEPS_MAX, p->bwd_steps / (N_CU * 8)));
+    auto cost = [&](const BwdUnit &u) { return int64_t(u.slot_end - u.slot_begin) / BWD_BQ * g; };
+    struct Chain {
+      size_t a, b;  // tiles [a, b) of the sorted list
+      int64_t steps;
+    };
+    std::vector<Chain> chains;
+    for (size_t a = 0; a < btiles.size();) {
+      size_t b = a + 1;
+      int64_t sum = cost(btiles[a]);
+      if (sum <= CHAIN_UNIT_STEPS)
+        while (b < btiles.size() && sum + cost(btiles[b]) <= target && int64_t(b - a) < CHAIN_UNITS_MAX)
+          sum += cost(btiles[b++]);
+      chains.push_back({a, b, sum});
+      a = b;
     }
+    // workgroups are handed out in index order: longest first, a chain counting with all its steps
+    std::stable_sort(chains.begin(), chains.end(), [](const Chain &x, const Chain &y) { return x.steps > y.steps; });
+    size_t first_chain = chains.size();
+    for (size_t ci = chains.size(); ci-- > 0;)
+      if (chains[ci].b - chains[ci].a > 1) first_chain = ci;
+    p->bwd_workgroups = int32_t(chains.size() * hkv);
+    p->bwd_units.resize(size_t(p->bwd_workgroups));
+    p->bwd_units.reserve(btiles.size() * hkv);
+    p->bwd_single = int32_t(first_chain * hkv);
+    for (size_t ci = 0; ci < chains.size(); ++ci) {
+      const size_t a = chains[ci].a, b = chains[ci].b;
+      for (int h = 0; h < hkv; ++h) {
+        BwdUnit u = btiles[a];
+        u.kv_head = h;
+        u.count = int32_t(b - a);
+        u.follow = b - a > 1 ? int32_t(p->bwd_units.size()) : 0;
+        p->bwd_units[ci * hkv + h] = u;
+        for (size_t t = a + 1; t < b; ++t) {
+          BwdUnit f = btiles[t];
+          f.kv_head = h;
+          p->bwd_units.push_back(f);
+        }
+      }
+    }
+  }
   p->q_covered = covered_q == p->total_q;
   p->kv_covered = covered_kv == p->total_kv;
   // workspace of backward, all in slot order: per (head, slot) fp32 -Delta and log2(e)*LSE, then bf16 copies of Q
@@ -222,13 +263,13 @@ void schedule(ca_plan_t *p) {
   p->ws_off_l2 = per;
   p->ws_off_qs = 2 * per;
   p->ws_off_dos = 2 * per + copy;
-  // ... and one progress counter per backward unit (plus a block of zeros), by which the dK/dV workgroups that walk
+  // ... and one progress counter per backward workgroup (plus a block of zeros), by which the dK/dV workgroups that walk
   // the same Q/dO tiles keep within an L2 window of each other.  Workgroups go to the 8 XCDs round robin in index
   // order (workgroup i to XCD (i + c) mod 8) and unit i has KV head i mod n_kv_heads, so units lcm(8, n_kv_heads)
   // apart share both.
   p->ws_off_prog = 2 * per + 2 * copy;
   p->peer_stride = int(std::lcm<int64_t>(8, hkv));
-  p->ws_bwd = p->ws_off_prog + (p->bwd_units.size() + 64) * sizeof(int32_t);
+  p->ws_bwd = p->ws_off_prog + (size_t(p->bwd_workgroups) + 64) * sizeof(int32_t);
   p->ws_bwd = (p->ws_bwd + 255) / 256 * 256;
   p->ws_fwd = 0;
 }
@@ -307,11 +348,11 @@ int ca_plan_info(const ca_plan_t *p, int64_t *out, int n) {
   if (!p) return 0;
   int64_t full_tiles = 0;
   for (auto &u : p->fwd_units) full_tiles += u.hp == 1 && u.head == 0;
-  const int64_t v[12] = {ca::FWD_BM, full_tiles, int64_t(p->fwd_units.size()),
+  const int64_t v[13] = {ca::FWD_BM, full_tiles, int64_t(p->fwd_units.size()),
                          ca::BWD_BN, int64_t(p->bwd_units.size()), ca::FWD_BN, int64_t(p->slot_row.size()),
-                         p->fwd_steps, p->bwd_steps, ca::BWD_BQ, p->slot_align, p->heads_packed};
-  for (int i = 0; i < n && i < 12 && out; ++i) out[i] = v[i];
-  return 12;
+                         p->fwd_steps, p->bwd_steps, ca::BWD_BQ, p->slot_align, p->heads_packed, p->bwd_workgroups};
+  for (int i = 0; i < n && i < 13 && out; ++i) out[i] = v[i];
+  return 13;
 }
 
 int64_t ca_plan_rows(const ca_plan_t *p, int32_t *rows, int32_t *pos) {

@@ -21,8 +21,10 @@ def test_mfma_chains_are_left_alone_until_they_end(bwd_asm):
     assert len(bodies) == 2  # head_dim 128 and 64
     for body in bodies:
         n, marks, bad = C.check_mfma_chains(body)
-        # chains before the loop, in the loop (two, ended by markers) and on the diagonal
-        assert n >= 4 and marks == 2
+        # the kernel holds its body twice (units that run alone, chains of units).  Per body: chains before the loop, in
+        # the loop (two, ended by markers) and on the diagonal; the compiler may keep two copies of a loop (one per
+        # value of a condition that does not change inside it)
+        assert n >= 8 and marks in (4, 6, 8)
         assert not bad, bad
 
 

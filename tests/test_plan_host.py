@@ -125,12 +125,31 @@ def check_schedule(b):
     # backward units: every key of every scheduled document once per KV head
     bu = p.bwd_units()
     assert len(bu) == info["n_bwd_units"]
+    # the leading units are one workgroup each, longest first; a workgroup goes on with the units it points to
+    n_wg = info["n_bwd_workgroups"]
+    assert 0 <= n_wg <= len(bu) and (n_wg > 0) == (len(bu) > 0)
     span = bu[:, 1] - bu[:, 0]
-    assert np.all(np.diff(span) <= 0), "longest first"
+    assert np.all(bu[:n_wg, 8] >= 1) and np.all(bu[n_wg:, 8] == 0) and bu[:, 8].sum() == len(bu)
+    followed = np.zeros(len(bu), np.int32)
+    steps = span // bq * g
+    wg_steps = np.zeros(n_wg, np.int64)
+    for i in range(n_wg):
+        assert i % b.n_kv_heads == bu[i, 6], "workgroup index modulo n_kv_heads is the KV head"
+        f, c = int(bu[i, 7]), int(bu[i, 8])
+        wg_steps[i] = steps[i] + (steps[f:f + c - 1].sum() if c > 1 else 0)
+        if c > 1:
+            assert n_wg <= f and f + c - 1 <= len(bu)
+            followed[f:f + c - 1] += 1
+            chain = np.concatenate([[i], np.arange(f, f + c - 1)])
+            assert np.all(bu[chain, 6] == bu[i, 6]), "a chain stays with one KV head"
+            assert np.all(np.diff(span[chain]) <= 0)
+            assert steps[chain].max() <= 16 and steps[chain].sum() <= 128 and c <= 16, "only short units are chained"
+    assert np.all(np.diff(wg_steps) <= 0), "longest first, a chain counting with all its steps"
+    assert np.all(followed[n_wg:] == 1) and np.all(followed[:n_wg] == 0), "every following unit belongs to one chain"
     key_cover = np.zeros((b.total_kv, b.n_kv_heads), np.int32)
     docs_with_tasks = sorted(set(b.task_doc.tolist()))
-    for i, (sb, se, sf, kvrow, nvalid, kp0, hk) in enumerate(bu.tolist()):
-        assert i % b.n_kv_heads == hk and 1 <= nvalid <= bn and (se - sb) % bq == 0 and se >= sb
+    for i, (sb, se, sf, kvrow, nvalid, kp0, hk, _, _) in enumerate(bu.tolist()):
+        assert 0 <= hk < b.n_kv_heads and 1 <= nvalid <= bn and (se - sb) % bq == 0 and se >= sb
         assert sb <= sf <= se and (sf - sb) % bq == 0
         assert np.all(pos[sf:se] >= kp0 + bn - 1), "blocks from slot_full on see every key of the tile"
         if sf - bq >= sb:
