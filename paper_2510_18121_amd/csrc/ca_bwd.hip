@@ -280,7 +280,12 @@ struct DkvSmem {
   static constexpr int POS_OFF = DL_OFF + 256;
   static constexpr int SPARE_OFF = POS_OFF + 256;
   static constexpr int STAGE = 2 * TILE + 1024;
-  static constexpr int TOTAL = NST * STAGE;
+  // behind the stages: one patch per wave through which it turns its results into whole rows (32 keys x 64 values of
+  // 2 bytes, rows 16 bytes apart from a power of two)
+  static constexpr int OUT_OFF = NST * STAGE;
+  static constexpr int OUT_ROWB = 128 + 16;
+  static constexpr int OUT_WAVE = 32 * OUT_ROWB;
+  static constexpr int TOTAL = OUT_OFF + 4 * OUT_WAVE;
 };
 
 template <int D, bool CHAIN>
@@ -822,19 +827,37 @@ __device__ __forceinline__ void dkv_workgroup(const int me, const BwdUnit &first
     for (int s = 0; s < NS; ++s) pin_acc(kf[s]), pin_acc(vf[s]);
   }
 
-  // ---- write dK (scaled) and dV of the wave's 32 keys
-  if (kw0 + r < u.n_valid) {
-    const size_t off = (size_t(u.kv_row + kw0 + r) * Hkv + hk) * D + 4 * g;
+  // ---- write dK (scaled) and dV of the wave's 32 keys.  A lane holds, of its key's row, 4 values out of every 8:
+  // stored from there, one instruction would touch 32 rows with 16 bytes each, and the 64 of them per wave keep the
+  // CU's address unit busy for longer than a short unit's steps take.  So the wave passes 64 values per key at a
+  // time through its LDS patch (in-order per wave: no synchronisation) and stores whole 128-byte lines, 8 rows per
+  // instruction.
+  {
+    const uint32_t patch = lds0 + S::OUT_OFF + wave * S::OUT_WAVE;
+    const uint32_t wr = patch + r * S::OUT_ROWB + 8 * g;  // + 64 (b & 1) + 16 q4: values 32 b + 8 q4 + 4 g .. + 3
+    const int orow = lane >> 3, ocol = lane & 7;          // the lane's row (+ 8 i) and 16-byte piece of the patch
+    const uint32_t rd = patch + orow * S::OUT_ROWB + 16 * ocol;
 #pragma unroll
-    for (int b = 0; b < NDB; ++b)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        u32x2 wk = {pack_bf16(acc_dk[b][4 * q4] * scale, acc_dk[b][4 * q4 + 1] * scale),
-                    pack_bf16(acc_dk[b][4 * q4 + 2] * scale, acc_dk[b][4 * q4 + 3] * scale)};
-        u32x2 wv = {pack_bf16(acc_dv[b][4 * q4], acc_dv[b][4 * q4 + 1]),
-                    pack_bf16(acc_dv[b][4 * q4 + 2], acc_dv[b][4 * q4 + 3])};
-        *reinterpret_cast<u32x2 *>(dK + off + 32 * b + 8 * q4) = wk;
-        *reinterpret_cast<u32x2 *>(dV + off + 32 * b + 8 * q4) = wv;
+      for (int h = 0; h < NDB / 2; ++h) {
+#pragma unroll
+        for (int bb = 0; bb < 2; ++bb)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const f32x16 &a = t == 0 ? acc_dk[2 * h + bb] : acc_dv[2 * h + bb];
+            const float f = t == 0 ? scale : 1.0f;
+            const u32x2 w = {pack_bf16(a[4 * q4] * f, a[4 * q4 + 1] * f), pack_bf16(a[4 * q4 + 2] * f, a[4 * q4 + 3] * f)};
+            *(CA_LDS u32x2 *)(wr + 64 * bb + 16 * q4) = w;
+          }
+        bf16_t *const out = t == 0 ? dK : dV;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const u32x4 x = *(const CA_LDS u32x4 *)(rd + 8 * i * S::OUT_ROWB);
+          const int key = kw0 + orow + 8 * i;
+          if (key < u.n_valid)
+            *reinterpret_cast<u32x4 *>(out + (size_t(u.kv_row + key) * Hkv + hk) * D + 64 * h + 8 * ocol) = x;
+        }
       }
   }
   // every wave is done with the LDS stages before a new stream refills them
