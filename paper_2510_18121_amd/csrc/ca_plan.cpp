@@ -208,12 +208,15 @@ void schedule(ca_plan_t *p) {
   {
     // Chains of the dK/dV kernel: consecutive KV tiles of the sorted list (equal or similar cost; the tiles of one
     // document under the same query rows are neighbours in it) whose units are short - at most CHAIN_UNIT_STEPS
-    // steps each: what chaining saves per unit is a few steps' worth - go to one workgroup per KV head, until the
-    // chain holds about 1/8 of a CU's share of the kernel's steps (so that at least 8 workgroups per CU remain for the
-    // dispatcher to balance with), at most CHAIN_STEPS_MAX steps and at most CHAIN_UNITS_MAX units.
-    constexpr int64_t N_CU = 256, CHAIN_UNIT_STEPS = 16, CHAIN_STEPS_MAX = 128, CHAIN_UNITS_MAX = 16;
-    const int64_t target = std::max<int64_t>(1, std::min<int64_t>(CHAIN_STEPS_MAX, p->bwd_steps / (N_CU * 8)));
+    // steps each: what chaining saves per unit is a few steps' worth - go to one workgroup per KV head.  A chain
+    // takes at most CHAIN_STEPS_MAX steps and CHAIN_UNITS_MAX units, and at most 1/(2 N_CU) of the short units' steps
+    // still to be handed out: chains shrink towards the end of the list, so that the last workgroups of the launch
+    // are small ones and the CUs finish together.
+    constexpr int64_t N_CU = 256, CHAIN_UNIT_STEPS = 16, CHAIN_STEPS_MAX = 256, CHAIN_UNITS_MAX = 32;
     auto cost = [&](const BwdUnit &u) { return int64_t(u.slot_end - u.slot_begin) / BWD_BQ * g; };
+    int64_t remaining = 0;  // steps of short units, all KV heads
+    for (auto &t : btiles)
+      if (cost(t) <= CHAIN_UNIT_STEPS) remaining += cost(t) * hkv;
     struct Chain {
       size_t a, b;  // tiles [a, b) of the sorted list
       int64_t steps;
@@ -222,9 +225,12 @@ void schedule(ca_plan_t *p) {
     for (size_t a = 0; a < btiles.size();) {
       size_t b = a + 1;
       int64_t sum = cost(btiles[a]);
-      if (sum <= CHAIN_UNIT_STEPS)
+      if (sum <= CHAIN_UNIT_STEPS) {
+        const int64_t target = std::min<int64_t>(CHAIN_STEPS_MAX, remaining / (2 * N_CU));
         while (b < btiles.size() && sum + cost(btiles[b]) <= target && int64_t(b - a) < CHAIN_UNITS_MAX)
           sum += cost(btiles[b++]);
+        remaining -= sum * hkv;
+      }
       chains.push_back({a, b, sum});
       a = b;
     }

@@ -143,7 +143,7 @@ def check_schedule(b):
             chain = np.concatenate([[i], np.arange(f, f + c - 1)])
             assert np.all(bu[chain, 6] == bu[i, 6]), "a chain stays with one KV head"
             assert np.all(np.diff(span[chain]) <= 0)
-            assert steps[chain].max() <= 16 and steps[chain].sum() <= 128 and c <= 16, "only short units are chained"
+            assert steps[chain].max() <= 16 and steps[chain].sum() <= 256 and c <= 32, "only short units are chained"
     assert np.all(np.diff(wg_steps) <= 0), "longest first, a chain counting with all its steps"
     assert np.all(followed[n_wg:] == 1) and np.all(followed[:n_wg] == 0), "every following unit belongs to one chain"
     key_cover = np.zeros((b.total_kv, b.n_kv_heads), np.int32)
