@@ -260,9 +260,11 @@ def check_sampled_rows(batch, tensors, hip, rows, kv_head):
             "dq_rel_l2": rel_l2(dq, ref["dq"]), "dq_row_rel_l2": row, "rows": int(len(rows))}
 
 
-def check_key_gradients(batch, tensors, hip, kv_head, short_doc_max=2048, tail_keys=512):
+def check_key_gradients(batch, tensors, hip, kv_head, short_doc_max=2048, tail_keys=512, require_full=True):
     """dK/dV exactly for (a) every document of at most short_doc_max keys, whole, and (b) the last tail_keys
-    keys of the longest document (only the query rows at those positions see them)."""
+    keys of the longest document (only the query rows at those positions see them).  With require_full, only
+    documents all of whose rows are in the batch; without, also documents present with some of their rows (a shard
+    and its context: the gradient of its keys is what those rows contribute)."""
     q, k, v, d_o = tensors
     task, doc, pos = _row_owner(batch)
     g = batch.n_q_heads // batch.n_kv_heads
@@ -303,7 +305,8 @@ def check_key_gradients(batch, tensors, hip, kv_head, short_doc_max=2048, tail_k
         out[tag + "_keys"] = int(sum(len(x) for x in dk_r))
 
     present = sorted(set(batch.task_doc.tolist()))
-    full = {d for d in present if sum(int(batch.task_q_len[t]) for t in np.flatnonzero(batch.task_doc == d)) == int(batch.doc_kv_len[d])}
+    full = {d for d in present if not require_full or
+            sum(int(batch.task_q_len[t]) for t in np.flatnonzero(batch.task_doc == d)) == int(batch.doc_kv_len[d])}
     short = [d for d in present if batch.doc_kv_len[d] <= short_doc_max and d in full]
     if short:
         run(short, {d: 0 for d in short}, "short_docs")

@@ -23,6 +23,47 @@ def test_shard_chunks_match_the_oracle(mode, n, ctx):
     P.assert_parity(e, b.name)
 
 
+@pytest.mark.parametrize("hq,hkv,d,n,ctx,chunk", [(8, 2, 128, 64, 1536, 8192), (8, 1, 128, 64, 1024, 16384),
+                                                   (8, 2, 64, 64, 1536, 8192), (4, 1, 128, 128, 2048, 24576),
+                                                   (8, 2, 128, 32, 1536, 4096), (6, 2, 128, 64, 1536, 12288)])
+def test_chained_short_units_match_the_oracle(hq, hkv, d, n, ctx, chunk):
+    """Lone shards with a context, all tensors: every (KV tile, KV head) unit of the dK/dV kernel is a few steps, so
+    the planner chains them.  Inside one document the Q/dO stream runs on from unit to unit; with 3 or more steps per
+    unit (4 or 8 heads per group, or two query blocks) K and V are fetched a unit ahead, also across documents, where
+    the stream starts again; with 3 heads per group (2 steps) the stream runs on without the fetch."""
+    from paper_2510_18121_amd import binding as B
+    b = W.shard_chunk(n, "distinct", seed=5, chunk_tokens=chunk, max_context=ctx, hq=hq, hkv=hkv, d=d)
+    info = B.ca_plan_host(b).info()
+    assert info["n_bwd_workgroups"] < info["n_bwd_units"], "units are chained"
+    q, k, v, d_o = W.make_tensors(b, DEV)
+    e = P.errors(P.run_hip(b, q, k, v, d_o), P.run_oracle(b, q, k, v, d_o))
+    print(b.name, b.n_tasks, "tasks", info["n_bwd_units"], "units in", info["n_bwd_workgroups"], "workgroups", e, flush=True)
+    P.assert_parity(e, b.name)
+
+
+@pytest.mark.parametrize("n", [64, 128])
+def test_full_size_shard_chunk_on_exact_subproblems(n):
+    """A chunk of the shard-length experiment at its full size (32K tokens, contexts up to 16K: chains of up to 32
+    units): sampled query rows, the key gradients of every document of at most 2048 keys and of the last keys of the
+    longest one for one KV head, and the sum identities over the whole output."""
+    b = W.shard_chunk(n, "distinct", seed=0)
+    tensors = W.make_tensors(b, DEV)
+    hip = P.run_hip(b, *tensors)
+    rows = P.sample_rows(b, 192, seed=n)
+    e = P.check_sampled_rows(b, tensors, hip, rows, kv_head=n % b.n_kv_heads)
+    e.update(P.check_key_gradients(b, tensors, hip, kv_head=(n // 64) % b.n_kv_heads, tail_keys=256, require_full=False))
+    e.update(P.sum_invariants(b, tensors[3], hip))
+    print(b.name, e, flush=True)
+    assert e["o_err_over_bound"] <= 1.0 and e["lse_max_abs"] <= P.LSE_MAX_ABS and e["dq_rel_l2"] <= P.GRAD_REL_L2
+    for key, val in e.items():
+        if key.endswith("row_rel_l2"):
+            assert val <= P.ROW_REL_L2, (key, val)
+        elif key.endswith("rel_l2"):
+            assert val <= P.GRAD_REL_L2, (key, val)
+    assert e["sum_dv_minus_sum_do_rel"] <= P.SUM_INVARIANT and e["sum_dk_rel"] <= P.SUM_INVARIANT, e
+    assert e["short_docs_keys"] >= 16384 and e["tail_keys"] > 0 and e["rows"] >= 192
+
+
 def test_latency_grid_predicts_unmeasured_tasks():
     """A coarse grid measured on this GPU; tasks between grid points are then timed and compared with the model's
     prediction (bilinear in latency between grid points a factor of four apart: within 15 %; the model's arithmetic is

@@ -173,6 +173,20 @@ def check_schedule(b):
     return p
 
 
+def test_short_backward_units_are_chained():
+    """Lone 64-token shards with contexts: units of 4 steps, chained per KV head; long documents: none chained."""
+    b = W.shard_chunk(64, "distinct", seed=1, chunk_tokens=4096, max_context=2048, hq=8, hkv=2, d=128)
+    p = check_schedule(b)
+    info, bu = p.info(), p.bwd_units()
+    n_wg = info["n_bwd_workgroups"]
+    assert n_wg < len(bu) and bu[:n_wg, 8].max() > 1
+    # chains shrink towards the end of the list: the last workgroups are single units or short chains
+    assert bu[n_wg - 1, 8] <= 2 <= bu[0, 8]
+    long_docs = W.config(4, downscale=16)
+    info = B.ca_plan_host(long_docs).info()
+    assert info["n_bwd_workgroups"] >= info["n_bwd_units"] - 64
+
+
 def test_schedule_invariants_small_and_ragged():
     check_schedule(base())
     check_schedule(W.config(1))
