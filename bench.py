@@ -23,7 +23,7 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 # HBM bytes per launch of the dK/dV kernel on workload 3 as counted by rocprofv3 (FETCH_SIZE / WRITE_SIZE passes,
 # scaled by the plain-copy calibration): NOT measured in a plain run of this script.  The figure of the last counter
 # passes is quoted under roofline.traffic_profiled with the file it comes from; roofline.traffic itself is null.
-DKV_TRAFFIC_PROFILED = {"bytes": int((47.3 + 0.56) * 2**30), "workload": 3,
+DKV_TRAFFIC_PROFILED = {"bytes": int((44.3 + 0.56) * 2**30), "workload": 3,
                         "source": "profiles/hot_path_cfg3_hbm_traffic.md"}
 
 
