@@ -245,12 +245,14 @@ int ca_plan_info(const ca_plan_t *plan, int64_t *out, int n);
  *                             heads per unit hp}: a unit is one workgroup of the forward and dQ kernels and
  *                             covers 256 / hp slots of hp consecutive query heads of one KV group; hp = 1 for the
  *                             full 256-slot tiles of a document, heads_packed for the slots left over
- *  bwd  : [n_bwd_units][9] = {first slot of first q block, slots end, first slot from which every slot sees the
+ *  bwd  : [n_bwd_units][10] = {first slot of first q block, slots end, first slot from which every slot sees the
  *                             whole tile, packed KV row of the tile's first key, valid keys in tile, document
- *                             position of the tile's first key, KV head, follow, count}.  The first
+ *                             position of the tile's first key, KV head, follow, count, tiles per q block}.  The first
  *                             n_bwd_workgroups units are one workgroup of the dK/dV kernel each (longest first; unit
  *                             index modulo n_kv_heads = KV head); such a unit has count >= 1, and its workgroup goes
- *                             on with the count - 1 units stored from index `follow` on (same KV head, count 0)
+ *                             on with the count - 1 units stored from index `follow` on (same KV head, count 0).
+ *                             Tiles per q block = the query heads per KV head, or a half or a quarter of that for a
+ *                             document of at most 32 / 16 rows, whose 64-row tiles hold the rows of 2 / 4 heads
  */
 int64_t ca_plan_rows(const ca_plan_t *plan, int32_t *rows, int32_t *pos);
 int64_t ca_plan_fwd_units(const ca_plan_t *plan, int32_t *units);

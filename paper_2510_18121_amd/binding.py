@@ -146,7 +146,7 @@ class Plan:
 
     def bwd_units(self):
         n = lib().ca_plan_bwd_units(self.handle, None)
-        u = np.zeros((n, 9), np.int32)
+        u = np.zeros((n, 10), np.int32)
         lib().ca_plan_bwd_units(self.handle, u.ctypes.data)
         return u
 

@@ -57,6 +57,9 @@ static void free_device(ca_plan_t *p) {
   if (hipGetDevice(&cur) == hipSuccess && cur != p->device) (void)hipSetDevice(p->device);
   if (p->d_slot_row) (void)hipFree(p->d_slot_row);
   if (p->d_slot_pos) (void)hipFree(p->d_slot_pos);
+  if (p->d_block_rpk) (void)hipFree(p->d_block_rpk);
+  if (p->d_pos_kv) (void)hipFree(p->d_pos_kv);
+  p->d_block_rpk = p->d_pos_kv = nullptr;
   if (p->d_fwd_units) (void)hipFree(p->d_fwd_units);
   if (p->d_bwd_units) (void)hipFree(p->d_bwd_units);
   p->d_slot_row = p->d_slot_pos = nullptr;
@@ -120,6 +123,7 @@ int ca_plan_upload(ca_plan_t *p, void *hip_stream) {
   };
   hipError_t e;
   if ((e = up(p->d_slot_row, p->slot_row)) != hipSuccess || (e = up(p->d_slot_pos, p->slot_pos)) != hipSuccess ||
+      (e = up(p->d_block_rpk, p->block_rpk)) != hipSuccess || (e = up(p->d_pos_kv, p->pos_kv)) != hipSuccess ||
       (e = up(p->d_fwd_units, p->fwd_units)) != hipSuccess || (e = up(p->d_bwd_units, p->bwd_units)) != hipSuccess) {
     free_device(p);
     return hip_fail("plan upload", e);

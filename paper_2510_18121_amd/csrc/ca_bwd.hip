@@ -28,16 +28,20 @@ namespace ca {
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float L2_PADDING = 1.0e30f;  // exp2(x - 1e30) == 0 for every finite score
 
-__global__ void ca_bwd_prep_kernel(const int32_t *__restrict__ slot_row, const bf16_t *__restrict__ Q,
-                                   const bf16_t *__restrict__ O, const bf16_t *__restrict__ dO,
-                                   const float *__restrict__ LSE, float *__restrict__ delta_slot,
-                                   float *__restrict__ l2_slot, bf16_t *__restrict__ q_sorted,
-                                   bf16_t *__restrict__ do_sorted, int32_t *__restrict__ progress, int n_progress,
-                                   int64_t padded, int64_t total_q, int Hq, int D) {
-  // D/8 lanes per (slot, head): -Delta = -<dO, O> and log2(e)*LSE in slot order, and the slot-ordered copies of
-  // Q and dO as [block of 64 slots][head][64][D]: the 64-slot tile of a (block, head) is one contiguous run, and
-  // the tiles of the heads of a block follow each other (padding slots: zeros, with an LSE that makes every
-  // probability 0)
+__global__ void ca_bwd_prep_kernel(const int32_t *__restrict__ slot_row, const int32_t *__restrict__ block_rpk,
+                                   const bf16_t *__restrict__ Q, const bf16_t *__restrict__ O,
+                                   const bf16_t *__restrict__ dO, const float *__restrict__ LSE,
+                                   float *__restrict__ delta_slot, float *__restrict__ l2_slot,
+                                   float *__restrict__ delta_kv, float *__restrict__ l2_kv,
+                                   bf16_t *__restrict__ q_sorted, bf16_t *__restrict__ do_sorted,
+                                   int32_t *__restrict__ progress, int n_progress, int64_t padded, int64_t total_q,
+                                   int Hq, int G, int D) {
+  // D/8 lanes per (slot, head): -Delta = -<dO, O> and log2(e)*LSE in slot order (for the dQ kernel), and for the
+  // dK/dV kernel the slot-ordered copies of Q and dO as [block of 64 slots][head][64][D] - the 64-row tile of a
+  // (block, head) is one contiguous run, and the tiles of the heads of a block follow each other - with the same two
+  // statistics in the row order of those tiles (padding rows: zeros, with an LSE that makes every probability 0).
+  // In a packed block (a document of at most rpk = 16 or 32 rows) tile t of a KV group holds the rows of the group's
+  // heads 64/rpk t .. 64/rpk (t + 1) - 1, rpk rows each; the group's remaining tiles are neither written nor read.
   const int lanes = D / 8;
   const int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
   if (idx < n_progress) progress[idx] = 0;  // progress counters of the dK/dV workgroups: nobody has started
@@ -60,12 +64,30 @@ __global__ void ca_bwd_prep_kernel(const int32_t *__restrict__ slot_row, const b
   }
   for (int o = lanes / 2; o > 0; o >>= 1) s += __shfl_xor(s, o);
   if (ok) {
-    const size_t so = ((size_t(slot / BWD_BQ) * Hq + h) * BWD_BQ + slot % BWD_BQ) * D + 8 * c;
-    *reinterpret_cast<u32x4 *>(q_sorted + so) = qv;
-    *reinterpret_cast<u32x4 *>(do_sorted + so) = dv;
+    const float nd = row >= 0 ? -s : 0.f;  // stored negated: both kernels add it
+    const float l2 = row >= 0 && c == 0 ? LSE[int64_t(h) * total_q + row] * LOG2E : L2_PADDING;
+    const int64_t blk = slot / BWD_BQ;
+    const int rpk = block_rpk[blk];
+    int th = h, tr = int(slot % BWD_BQ);  // tile (as a head index) and row of this (slot, head) in the dK/dV tiles
+    bool in_tile = true;
+    if (rpk != 0) {
+      const int hpk = BWD_BQ / rpk, hg = h % G;
+      in_tile = tr < rpk;  // the slots beyond are padding of the document
+      th = h - hg + hg / hpk;
+      tr += (hg % hpk) * rpk;
+    }
+    if (in_tile) {
+      const size_t so = ((size_t(blk) * Hq + th) * BWD_BQ + tr) * D + 8 * c;
+      *reinterpret_cast<u32x4 *>(q_sorted + so) = qv;
+      *reinterpret_cast<u32x4 *>(do_sorted + so) = dv;
+    }
     if (c == 0) {
-      delta_slot[int64_t(h) * padded + slot] = row >= 0 ? -s : 0.f;  // stored negated: both kernels add it
-      l2_slot[int64_t(h) * padded + slot] = row >= 0 ? LSE[int64_t(h) * total_q + row] * LOG2E : L2_PADDING;
+      delta_slot[int64_t(h) * padded + slot] = nd;
+      l2_slot[int64_t(h) * padded + slot] = l2;
+      if (in_tile) {
+        delta_kv[int64_t(th) * padded + blk * BWD_BQ + tr] = nd;
+        l2_kv[int64_t(th) * padded + blk * BWD_BQ + tr] = l2;
+      }
     }
   }
 }
@@ -345,16 +367,17 @@ __device__ __forceinline__ void dkv_workgroup(const int me, const BwdUnit &first
   const int hk = u.kv_head;
   const int key_pos = u.key_pos0 + kw0 + r;  // document position of this lane's key
   const int n_blocks = (u.slot_end - u.slot_begin) / BWD_BQ;
-  const int n_it = n_blocks * G;
+  const int Gu = u.heads;  // tiles per block: the heads of the group, or fewer in a block of packed rows
+  const int n_it = n_blocks * Gu;
   // Query blocks are walked from the last one backwards (below), so the blocks that lie entirely below the
   // diagonal of this KV tile come first: they take the pipelined path without mask.
-  const int n_fast = ((u.slot_end - u.slot_full) / BWD_BQ) * G;
+  const int n_fast = ((u.slot_end - u.slot_full) / BWD_BQ) * Gu;
   // the stream goes on into the next unit / the next unit's K and V are fetched ahead (the loads go out before the
-  // pipelined loop; the wait of its third step is the first that is certain to have seen all of them land.  Issued
-  // inside the loop, after its first wait, they would have longer to land, but the branch that takes costs every
-  // step of every unit more than it gains)
+  // pipelined loop and are waited for, by the compiler, where the fragments change hands at the unit's end; the
+  // loop's own waits count loads issued after them, so they can only wait longer.  Issued inside the loop, after its
+  // first wait, the loads would have longer to land, but the branch that takes costs every step more than it gains)
   const bool wrap = has_next && n_it > 0 && n_fast == n_it && nu.slot_begin == u.slot_begin && nu.slot_end == u.slot_end;
-  const bool fetch_kv = has_next && n_fast >= 3;
+  const bool fetch_kv = has_next && n_fast >= 1;
 
   // ---- loads of one (q block, head): this wave fetches tile rows RPW*wave .. +RPW-1 of Q and of dO, plus one
   // 64-float auxiliary array.  Q and dO come from their slot-ordered copies [block][head][64][D], in which the tile
@@ -432,14 +455,14 @@ __device__ __forceinline__ void dkv_workgroup(const int me, const BwdUnit &first
     load_lds4_at_fresh(aux_ptr, pst_addr + aux_lds);  // device scope for all four waves: no branch; the others' arrays are read once anyway
     pst = pst + 1 == NST ? 0 : pst + 1;
     pst_addr = pst == 0 ? lds0 : pst_addr + S::STAGE;
-    if (ph + 1 < G) {  // next head of the group, same block
+    if (ph + 1 < Gu) {  // next tile of the group, same block
       ++ph;
       q_tile += head_stride, do_tile += head_stride, aux_ptr += aux_hstride;
     } else if (pblk > 0) {  // first head of the group, previous block
       ph = 0;
       --pblk;
-      q_tile -= (G - 1) * head_stride + block_stride, do_tile -= (G - 1) * head_stride + block_stride;
-      aux_ptr -= (G - 1) * aux_hstride + aux_bstep;
+      q_tile -= (Gu - 1) * head_stride + block_stride, do_tile -= (Gu - 1) * head_stride + block_stride;
+      aux_ptr -= (Gu - 1) * aux_hstride + aux_bstep;
     } else if (wrap) {  // past the end: the next unit's first (block, head), which is this unit's
       ph = 0;
       pblk = n_blocks - 1;
@@ -917,6 +940,8 @@ static hipError_t launch_bwd_t(const ca_plan_t *p, const void *q, const void *k,
   const int64_t padded = int64_t(p->slot_row.size());
   float *delta_slot = static_cast<float *>(ws);
   float *l2_slot = reinterpret_cast<float *>(static_cast<char *>(ws) + p->ws_off_l2);
+  float *delta_kv = reinterpret_cast<float *>(static_cast<char *>(ws) + p->ws_off_delta_kv);
+  float *l2_kv = reinterpret_cast<float *>(static_cast<char *>(ws) + p->ws_off_l2_kv);
   bf16_t *q_sorted = reinterpret_cast<bf16_t *>(static_cast<char *>(ws) + p->ws_off_qs);
   bf16_t *do_sorted = reinterpret_cast<bf16_t *>(static_cast<char *>(ws) + p->ws_off_dos);
   int32_t *progress = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + p->ws_off_prog);
@@ -930,8 +955,9 @@ static hipError_t launch_bwd_t(const ca_plan_t *p, const void *q, const void *k,
     const int n_progress = p->bwd_workgroups + 64;
     const int64_t threads = std::max<int64_t>(padded * p->hq * (D / 8), n_progress);
     hipLaunchKernelGGL(ca_bwd_prep_kernel, dim3(unsigned((threads + 255) / 256)), dim3(256), 0, st, p->d_slot_row,
-                       static_cast<const bf16_t *>(q), static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(d_o),
-                       lse, delta_slot, l2_slot, q_sorted, do_sorted, progress, n_progress, padded, p->total_q, p->hq, D);
+                       p->d_block_rpk, static_cast<const bf16_t *>(q), static_cast<const bf16_t *>(o),
+                       static_cast<const bf16_t *>(d_o), lse, delta_slot, l2_slot, delta_kv, l2_kv, q_sorted, do_sorted,
+                       progress, n_progress, padded, p->total_q, p->hq, p->hq / p->hkv, D);
   }
   if (ev) (void)hipEventRecord(ev[1], st);
   if (!p->bwd_units.empty()) {
@@ -940,8 +966,8 @@ static hipError_t launch_bwd_t(const ca_plan_t *p, const void *q, const void *k,
     hipError_t e = set_smem(kern, DkvSmem<D>::TOTAL, p->device, done);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(unsigned(p->bwd_workgroups)), dim3(256), DkvSmem<D>::TOTAL, st, p->d_bwd_units,
-                       p->bwd_single, p->d_slot_pos, q_sorted, static_cast<const bf16_t *>(k),
-                       static_cast<const bf16_t *>(v), do_sorted, l2_slot, delta_slot, static_cast<bf16_t *>(dk),
+                       p->bwd_single, p->d_pos_kv, q_sorted, static_cast<const bf16_t *>(k),
+                       static_cast<const bf16_t *>(v), do_sorted, l2_kv, delta_kv, static_cast<bf16_t *>(dk),
                        static_cast<bf16_t *>(dv), progress, p->peer_stride, p->hq, p->hkv, padded, p->scale);
   }
   if (ev) (void)hipEventRecord(ev[2], st);

@@ -43,6 +43,9 @@ struct BwdUnit {  // one (KV tile, KV head)
   // (filling the pipeline, fetching K and V, draining) can then overlap with the steps of its neighbours.
   int32_t follow;
   int32_t count;  // units of this workgroup including this one; 0 in a unit that follows another
+  // (block, head) tiles per query block: the heads of the KV group, or fewer where a document of at most 32 rows has
+  // the rows of 2 or 4 heads packed into each 64-row tile (the heads of a group add into the same dK and dV)
+  int32_t heads;
 };
 
 }  // namespace ca
@@ -56,6 +59,9 @@ struct ca_plan {
   std::vector<int32_t> task_doc;
   // schedule (host)
   std::vector<int32_t> slot_row, slot_pos;
+  // for the dK/dV kernel: rows per head in the packed tiles of a 64-slot block (16 or 32; 0 = one head per tile), and
+  // the position of every row of its tiles (= slot_pos except in packed blocks)
+  std::vector<int32_t> block_rpk, pos_kv;
   std::vector<ca::FwdUnit> fwd_units;
   std::vector<ca::BwdUnit> bwd_units;
   int32_t bwd_workgroups = 0;  // workgroups of the dK/dV kernel: the leading units of bwd_units
@@ -64,11 +70,12 @@ struct ca_plan {
   // workspace layout for backward: [Delta fp32 hq*padded_slots][log2e*LSE fp32 hq*padded_slots]
   int slot_align = ca::SLOT_ALIGN, heads_packed = 1;  // padding of a document's slots; hp of the packed units
   size_t ws_fwd = 0, ws_bwd = 0, ws_off_l2 = 0, ws_off_qs = 0, ws_off_dos = 0, ws_off_prog = 0;
+  size_t ws_off_delta_kv = 0, ws_off_l2_kv = 0;  // the row statistics once more, in the row order of the dK/dV tiles
   int peer_stride = 8;  // distance, in backward units, between units of one KV head that run on one XCD
   bool q_covered = false, kv_covered = false;  // every packed Q row / KV row belongs to some unit
   // device copies
   int device = -1;
-  int32_t *d_slot_row = nullptr, *d_slot_pos = nullptr;
+  int32_t *d_slot_row = nullptr, *d_slot_pos = nullptr, *d_block_rpk = nullptr, *d_pos_kv = nullptr;
   ca::FwdUnit *d_fwd_units = nullptr;
   ca::BwdUnit *d_bwd_units = nullptr;
   // optional timing events (hipEvent_t, kept as void* so that host-only code needs no HIP header)

@@ -115,6 +115,7 @@ void schedule(ca_plan_t *p) {
   CA_REQUIRE(padded < (int64_t(1) << 31) - SLOT_ALIGN, CA_ERR_UNSUPPORTED, "too many padded query rows");
   p->slot_row.assign(padded, -1);
   p->slot_pos.assign(padded, 0);
+  p->block_rpk.assign(padded / BWD_BQ, 0);
 
   struct TileRef {
     int32_t cost;
@@ -148,6 +149,12 @@ void schedule(ca_plan_t *p) {
       for (int64_t i = s0; i < s; ++i) p->slot_pos[i] = rows[i - s0].pos, p->slot_row[i] = rows[i - s0].row;
     }
     const int32_t last_pos = p->slot_pos[s - 1];
+    // A document that brings at most 32 rows: the dK/dV kernel's 64-row tiles of its one query block take the rows of
+    // 4 heads (16 rows each) or 2 heads (32 rows each) of the KV group instead of one head's rows and padding.
+    const int64_t n_rows = s - s0;
+    const int rpk = n_rows <= 16 && g % 4 == 0 ? 16 : n_rows <= 32 && g % 2 == 0 ? 32 : 0;
+    const int32_t tiles_per_block = rpk ? g / (BWD_BQ / rpk) : g;
+    if (rpk) p->block_rpk[s0 / BWD_BQ] = rpk;
     const int64_t s1 = round_up(s - s0, align) + s0;
     for (; s < s1; ++s) p->slot_pos[s] = last_pos;  // padding slots: row -1, position of the last real row
     const int32_t kv_row0 = int32_t(p->doc_kv_start[dd]);
@@ -169,6 +176,7 @@ void schedule(ca_plan_t *p) {
     const int32_t doc_len = int32_t(p->doc_kv_len[dd]);
     for (int32_t k0 = 0; k0 < doc_len; k0 += BWD_BN) {
       BwdUnit u{int32_t(s1), int32_t(s1), int32_t(s1), kv_row0 + k0, std::min<int32_t>(BWD_BN, doc_len - k0), k0, 0};
+      u.heads = tiles_per_block;
       if (k0 < cover) {
         // first slot whose position can see key k0
         const int32_t *b = p->slot_pos.data() + s0, *e = p->slot_pos.data() + s1;
@@ -201,10 +209,14 @@ void schedule(ca_plan_t *p) {
       p->fwd_steps += t.cost;
     }
   std::stable_sort(btiles.begin(), btiles.end(), [](const BwdUnit &a, const BwdUnit &b) {
-    return (a.slot_end - a.slot_begin) > (b.slot_end - b.slot_begin);
+    return int64_t(a.slot_end - a.slot_begin) * a.heads > int64_t(b.slot_end - b.slot_begin) * b.heads;
   });
+  p->pos_kv = p->slot_pos;
+  for (size_t blk = 0; blk < p->block_rpk.size(); ++blk)
+    if (const int rpk = p->block_rpk[blk])
+      for (int i = 0; i < BWD_BQ; ++i) p->pos_kv[blk * BWD_BQ + i] = p->slot_pos[blk * BWD_BQ + i % rpk];
   p->bwd_steps = 0;
-  for (auto &t : btiles) p->bwd_steps += int64_t(t.slot_end - t.slot_begin) / BWD_BQ * g * hkv;
+  for (auto &t : btiles) p->bwd_steps += int64_t(t.slot_end - t.slot_begin) / BWD_BQ * t.heads * hkv;
   {
     // Chains of the dK/dV kernel: consecutive KV tiles of the sorted list (equal or similar cost; the tiles of one
     // document under the same query rows are neighbours in it) whose units are short - at most CHAIN_UNIT_STEPS
@@ -213,7 +225,7 @@ void schedule(ca_plan_t *p) {
     // still to be handed out: chains shrink towards the end of the list, so that the last workgroups of the launch
     // are small ones and the CUs finish together.
     constexpr int64_t N_CU = 256, CHAIN_UNIT_STEPS = 16, CHAIN_STEPS_MAX = 256, CHAIN_UNITS_MAX = 32;
-    auto cost = [&](const BwdUnit &u) { return int64_t(u.slot_end - u.slot_begin) / BWD_BQ * g; };
+    auto cost = [&](const BwdUnit &u) { return int64_t(u.slot_end - u.slot_begin) / BWD_BQ * u.heads; };
     int64_t remaining = 0;  // steps of short units, all KV heads
     for (auto &t : btiles)
       if (cost(t) <= CHAIN_UNIT_STEPS) remaining += cost(t) * hkv;
@@ -273,7 +285,9 @@ void schedule(ca_plan_t *p) {
   // the same Q/dO tiles keep within an L2 window of each other.  Workgroups go to the 8 XCDs round robin in index
   // order (workgroup i to XCD (i + c) mod 8) and unit i has KV head i mod n_kv_heads, so units lcm(8, n_kv_heads)
   // apart share both.
-  p->ws_off_prog = 2 * per + 2 * copy;
+  p->ws_off_delta_kv = 2 * per + 2 * copy;
+  p->ws_off_l2_kv = 3 * per + 2 * copy;
+  p->ws_off_prog = 4 * per + 2 * copy;
   p->peer_stride = int(std::lcm<int64_t>(8, hkv));
   p->ws_bwd = p->ws_off_prog + (size_t(p->bwd_workgroups) + 64) * sizeof(int32_t);
   p->ws_bwd = (p->ws_bwd + 255) / 256 * 256;

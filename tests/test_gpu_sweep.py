@@ -25,12 +25,16 @@ def test_shard_chunks_match_the_oracle(mode, n, ctx):
 
 @pytest.mark.parametrize("hq,hkv,d,n,ctx,chunk", [(8, 2, 128, 64, 1536, 8192), (8, 1, 128, 64, 1024, 16384),
                                                    (8, 2, 64, 64, 1536, 8192), (4, 1, 128, 128, 2048, 24576),
-                                                   (8, 2, 128, 32, 1536, 4096), (6, 2, 128, 64, 1536, 12288)])
+                                                   (8, 2, 128, 32, 1536, 4096), (6, 2, 128, 64, 1536, 12288),
+                                                   (8, 2, 128, 16, 1536, 4096), (8, 1, 128, 16, 1024, 4096),
+                                                   (8, 2, 64, 24, 1536, 4080), (6, 2, 128, 16, 1536, 4096)])
 def test_chained_short_units_match_the_oracle(hq, hkv, d, n, ctx, chunk):
     """Lone shards with a context, all tensors: every (KV tile, KV head) unit of the dK/dV kernel is a few steps, so
     the planner chains them.  Inside one document the Q/dO stream runs on from unit to unit; with 3 or more steps per
     unit (4 or 8 heads per group, or two query blocks) K and V are fetched a unit ahead, also across documents, where
-    the stream starts again; with 3 heads per group (2 steps) the stream runs on without the fetch."""
+    the stream starts again; with 3 heads per group (2 steps) the stream runs on without the fetch.  Shards of at
+    most 32 / 16 rows have the rows of 2 / 4 heads of a group packed into each 64-row tile of the dK/dV kernel (not with 3
+    heads per group)."""
     from paper_2510_18121_amd import binding as B
     b = W.shard_chunk(n, "distinct", seed=5, chunk_tokens=chunk, max_context=ctx, hq=hq, hkv=hkv, d=d)
     info = B.ca_plan_host(b).info()

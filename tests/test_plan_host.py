@@ -131,7 +131,7 @@ def check_schedule(b):
     span = bu[:, 1] - bu[:, 0]
     assert np.all(bu[:n_wg, 8] >= 1) and np.all(bu[n_wg:, 8] == 0) and bu[:, 8].sum() == len(bu)
     followed = np.zeros(len(bu), np.int32)
-    steps = span // bq * g
+    steps = span // bq * bu[:, 9]
     wg_steps = np.zeros(n_wg, np.int64)
     for i in range(n_wg):
         assert i % b.n_kv_heads == bu[i, 6], "workgroup index modulo n_kv_heads is the KV head"
@@ -148,7 +148,7 @@ def check_schedule(b):
     assert np.all(followed[n_wg:] == 1) and np.all(followed[:n_wg] == 0), "every following unit belongs to one chain"
     key_cover = np.zeros((b.total_kv, b.n_kv_heads), np.int32)
     docs_with_tasks = sorted(set(b.task_doc.tolist()))
-    for i, (sb, se, sf, kvrow, nvalid, kp0, hk, _, _) in enumerate(bu.tolist()):
+    for i, (sb, se, sf, kvrow, nvalid, kp0, hk, _, _, tiles) in enumerate(bu.tolist()):
         assert 0 <= hk < b.n_kv_heads and 1 <= nvalid <= bn and (se - sb) % bq == 0 and se >= sb
         assert sb <= sf <= se and (sf - sb) % bq == 0
         assert np.all(pos[sf:se] >= kp0 + bn - 1), "blocks from slot_full on see every key of the tile"
@@ -157,6 +157,10 @@ def check_schedule(b):
         key_cover[kvrow:kvrow + nvalid, hk] += 1
         dd = [d for d in docs_with_tasks if b.doc_kv_start[d] <= kvrow < b.doc_kv_start[d] + b.doc_kv_len[d]][0]
         assert kvrow - b.doc_kv_start[dd] == kp0
+        # tiles per query block: one per head of the group, or the rows of 4 / 2 heads per tile for a document that brings
+        # at most 16 / 32 rows
+        n_doc_rows = int((real & (np.where(real, want_doc[np.maximum(rows, 0)], -1) == dd)).sum())
+        assert tiles == (g // 4 if n_doc_rows <= 16 and g % 4 == 0 else g // 2 if n_doc_rows <= 32 and g % 2 == 0 else g)
         # slots of this document that can see any key of the tile lie in [sb, se)
         doc_slots = np.flatnonzero(real & (np.where(real, want_doc[np.maximum(rows, 0)], -1) == dd))
         sees = doc_slots[pos[doc_slots] >= kp0]
