@@ -111,10 +111,11 @@ int ca_forward(const ca_plan_t *plan, const void *q, const void *k, const void *
  * ca_backward: dQ, dK, dV of L = sum(dO * O) given the forward's inputs and its saved O and LSE
  * (nothing else is kept between the two calls).  dq like q; dk, dv like k, v (every row written).
  * ws: device workspace of at least bwd_bytes, 256-byte aligned.  It receives, for every (query head, padded row
- * slot), fp32 -<dO, O> and log2(e)*LSE, and position-sorted bf16 copies of Q and dO
- * (bwd_bytes is about 2 * n_q_heads * padded_rows * (4 + 2 * head_dim) bytes: a little over the size of Q plus dO),
- * and one 4-byte progress counter per backward work unit, through which workgroups that read the same Q/dO tiles pace
- * each other (timing only).  No arithmetic uses atomics: results are bit-reproducible from run to run.  Allocates
+ * slot), fp32 -<dO, O> and log2(e)*LSE (twice: by head and slot, and in the row order of the dK/dV kernel's tiles), and
+ * position-sorted bf16 copies of Q and dO
+ * (bwd_bytes is about 4 * n_q_heads * padded_rows * (4 + head_dim) bytes: a little over the size of Q plus dO),
+ * and one 4-byte progress counter per workgroup of the dK/dV kernel, through which workgroups that read the same Q/dO
+ * tiles pace each other (timing only).  No arithmetic uses atomics: results are bit-reproducible from run to run.  Allocates
  * nothing, never synchronises.  Two calls whose workspaces overlap must not overlap in time on the device.
  */
 int ca_backward(const ca_plan_t *plan, const void *q, const void *k, const void *v, const void *o,
