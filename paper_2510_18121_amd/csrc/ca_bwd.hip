@@ -276,18 +276,14 @@ __global__ __launch_bounds__(512, 2) void ca_bwd_dq_kernel(const FwdUnit *__rest
     }
   }
   wait_vmcnt<0>();
-
-  if (row >= 0) {
-    bf16_t *op = dQ + (size_t(row) * Hq + head) * D + 4 * g;
-#pragma unroll
-    for (int b = 0; b < NDB; ++b)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        u32x2 w = {pack_bf16(acc[b][4 * q4] * scale, acc[b][4 * q4 + 1] * scale),
-                   pack_bf16(acc[b][4 * q4 + 2] * scale, acc[b][4 * q4 + 3] * scale)};
-        *reinterpret_cast<u32x2 *>(op + 32 * b + 8 * q4) = w;
-      }
-  }
+  // dQ of the wave's 32 rows, as whole lines through a patch of LDS (the stages are free once every wave is past its
+  // last tile)
+  __syncthreads();
+  static_assert(8 * PATCH_BYTES <= S::TOTAL, "patches fit in the stages");
+  store_tile_as_lines<NDB>(lds0 + wave * PATCH_BYTES, acc, scale, lane, [&](int p) __attribute__((always_inline)) -> bf16_t * {
+    const int rw = __shfl(row, p);
+    return rw >= 0 ? dQ + (size_t(rw) * Hq + head) * D : nullptr;
+  });
 }
 
 // ------------------------------------------------------------------------------------------------ dK, dV
@@ -302,12 +298,10 @@ struct DkvSmem {
   static constexpr int POS_OFF = DL_OFF + 256;
   static constexpr int SPARE_OFF = POS_OFF + 256;
   static constexpr int STAGE = 2 * TILE + 1024;
-  // behind the stages: one patch per wave through which it turns its results into whole rows (32 keys x 64 values of
-  // 2 bytes, rows 16 bytes apart from a power of two)
+  // behind the stages (which a chain keeps in use from unit to unit): one patch per wave through which it turns its
+  // results into whole rows
   static constexpr int OUT_OFF = NST * STAGE;
-  static constexpr int OUT_ROWB = 128 + 16;
-  static constexpr int OUT_WAVE = 32 * OUT_ROWB;
-  static constexpr int TOTAL = OUT_OFF + 4 * OUT_WAVE;
+  static constexpr int TOTAL = OUT_OFF + 4 * PATCH_BYTES;
 };
 
 template <int D, bool CHAIN>
@@ -850,16 +844,15 @@ __device__ __forceinline__ void dkv_workgroup(const int me, const BwdUnit &first
     for (int s = 0; s < NS; ++s) pin_acc(kf[s]), pin_acc(vf[s]);
   }
 
-  // ---- write dK (scaled) and dV of the wave's 32 keys.  A lane holds, of its key's row, 4 values out of every 8:
-  // stored from there, one instruction would touch 32 rows with 16 bytes each, and the 64 of them per wave keep the
-  // CU's address unit busy for longer than a short unit's steps take.  So the wave passes 64 values per key at a
-  // time through its LDS patch (in-order per wave: no synchronisation) and stores whole 128-byte lines, 8 rows per
-  // instruction.
+  // ---- write dK (scaled) and dV of the wave's 32 keys as whole lines through the wave's LDS patch, like
+  // store_tile_as_lines (stored straight from the accumulator layout, the 64 instructions per wave kept the CU's
+  // address unit busy for longer than a short unit's steps take).  Written out here, with the addresses formed after
+  // the LDS reads they wait for: the helper's order costs a chained unit a few tenths of a microsecond more.
   {
-    const uint32_t patch = lds0 + S::OUT_OFF + wave * S::OUT_WAVE;
-    const uint32_t wr = patch + r * S::OUT_ROWB + 8 * g;  // + 64 (b & 1) + 16 q4: values 32 b + 8 q4 + 4 g .. + 3
+    const uint32_t patch = lds0 + S::OUT_OFF + wave * PATCH_BYTES;
+    const uint32_t wr = patch + r * PATCH_ROW_BYTES + 8 * g;  // + 64 (b & 1) + 16 q4: values 32 b + 8 q4 + 4 g .. + 3
     const int orow = lane >> 3, ocol = lane & 7;          // the lane's row (+ 8 i) and 16-byte piece of the patch
-    const uint32_t rd = patch + orow * S::OUT_ROWB + 16 * ocol;
+    const uint32_t rd = patch + orow * PATCH_ROW_BYTES + 16 * ocol;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -876,7 +869,7 @@ __device__ __forceinline__ void dkv_workgroup(const int me, const BwdUnit &first
         bf16_t *const out = t == 0 ? dK : dV;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const u32x4 x = *(const CA_LDS u32x4 *)(rd + 8 * i * S::OUT_ROWB);
+          const u32x4 x = *(const CA_LDS u32x4 *)(rd + 8 * i * PATCH_ROW_BYTES);
           const int key = kw0 + orow + 8 * i;
           if (key < u.n_valid)
             *reinterpret_cast<u32x4 *>(out + (size_t(u.kv_row + key) * Hkv + hk) * D + 64 * h + 8 * ocol) = x;

@@ -271,4 +271,42 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("" ::: "memory");
 }
 
+
+// ---- a wave's 32 x D result tile, stored as whole lines.
+// In the accumulator layout of Xt = A B (32x32 MFMAs, 32-row blocks b of the D values) lane (r, g) holds, of row r
+// (a key, or a query row), the values 32 b + 8 q4 + 4 g .. + 3 in acc[b][4 q4 ..]: 4 values out of every 8.  Stored
+// from there, one instruction touches 32 rows with 16 bytes each, and the 16 D / 32 of them per tile keep a CU's address
+// unit busy for microseconds.  Instead the wave passes 64 values per row at a time through an LDS patch of its own
+// (PATCH_BYTES at `patch`, an LDS byte address; a wave's LDS instructions execute in order, so nothing synchronises)
+// and stores 8 rows x 128 bytes per instruction.  f scales the values (per lane, i.e. per row r); dst_of_row(p)
+// returns where row p (0..31) of the tile begins in memory, or nullptr for a row that is not stored.
+constexpr int PATCH_ROW_BYTES = 128 + 16;  // 16 bytes off a power of two
+constexpr int PATCH_BYTES = 32 * PATCH_ROW_BYTES;
+template <int NDB, class F>
+__device__ __forceinline__ void store_tile_as_lines(uint32_t patch, const f32x16 (&acc)[NDB], float f, int lane,
+                                                    F dst_of_row) {
+  const int r = lane & 31, g = lane >> 5, orow = lane >> 3, ocol = lane & 7;
+  const uint32_t wr = patch + r * PATCH_ROW_BYTES + 8 * g;  // + 64 (b & 1) + 16 q4
+  const uint32_t rd = patch + orow * PATCH_ROW_BYTES + 16 * ocol;  // the lane's row (+ 8 i) and 16-byte piece
+  bf16_t *dst[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) dst[i] = dst_of_row(orow + 8 * i);
+#pragma unroll
+  for (int h = 0; h < NDB / 2; ++h) {
+#pragma unroll
+    for (int bb = 0; bb < 2; ++bb)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x16 &a = acc[2 * h + bb];
+        const u32x2 w = {pack_bf16(a[4 * q4] * f, a[4 * q4 + 1] * f), pack_bf16(a[4 * q4 + 2] * f, a[4 * q4 + 3] * f)};
+        *(CA_LDS u32x2 *)(wr + 64 * bb + 16 * q4) = w;
+      }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const u32x4 x = *(const CA_LDS u32x4 *)(rd + 8 * i * PATCH_ROW_BYTES);
+      if (dst[i]) *reinterpret_cast<u32x4 *>(dst[i] + 64 * h + 8 * ocol) = x;
+    }
+  }
+}
+
 }  // namespace ca

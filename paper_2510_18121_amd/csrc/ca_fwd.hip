@@ -446,26 +446,22 @@ __global__ __launch_bounds__(64 * FWD_WAVES, 1) void ca_fwd_kernel(const FwdUnit
       advance_v();
     }
     wait_vmcnt<0>();
+    __syncthreads();  // the epilogue writes into the stages
   }
 
-  // epilogue: O = acc / l (bf16), LSE = ln 2 * (m + log2 l)
+  // epilogue: O = acc / l (bf16), LSE = ln 2 * (m + log2 l).  O leaves as whole lines through a patch of LDS (the
+  // stages are free: every wave is past its last tile)
+  static_assert(FWD_WAVES * PATCH_BYTES <= S::TOTAL, "patches fit in the stages");
 #pragma unroll
   for (int x = 0; x < 2; ++x) {
     float l = lsum[x];
     l += __shfl_xor(l, 32);
-    if (row[x] >= 0) {
-      const float inv = 1.0f / l;
-      bf16_t *op = O + (size_t(row[x]) * Hq + head[x]) * D + 4 * g;
-#pragma unroll
-      for (int b = 0; b < NDB; ++b)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          u32x2 w = {pack_bf16(acc[x][b][4 * q4] * inv, acc[x][b][4 * q4 + 1] * inv),
-                     pack_bf16(acc[x][b][4 * q4 + 2] * inv, acc[x][b][4 * q4 + 3] * inv)};
-          *reinterpret_cast<u32x2 *>(op + 32 * b + 8 * q4) = w;
-        }
-      if (g == 0) LSE[size_t(head[x]) * total_q + row[x]] = 0.6931471805599453f * (m[x] + fast_log2(l));
-    }
+    const int rx = row[x], hx = head[x];
+    store_tile_as_lines<NDB>(lds0 + wave * PATCH_BYTES, acc[x], 1.0f / l, lane, [&](int p) __attribute__((always_inline)) -> bf16_t * {
+      const int rw = __shfl(rx, p);
+      return rw >= 0 ? O + (size_t(rw) * Hq + hx) * D : nullptr;
+    });
+    if (rx >= 0 && g == 0) LSE[size_t(hx) * total_q + rx] = 0.6931471805599453f * (m[x] + fast_log2(l));
   }
 }
 
